@@ -1,0 +1,147 @@
+/*
+ * lda_mi355x.h -- C ABI of the MI355X (gfx950) LightLDA sweep library.
+ *
+ * The library runs the data-parallel hot path of LightLDA (arXiv 1412.1576):
+ * the O(1) cycle Metropolis-Hastings sweep over all tokens of a corpus
+ * (Sec. 4.2-4.3, Eq. 6-13), the per-word alias tables it draws from
+ * (Sec. 4.2, Fig. 2), and the rebuild of the count tables n_kd, n_kw, n_k
+ * (Sec. 3, text after Eq. 1).  Every step runs in hand-written HIP kernels on
+ * one GPU; the host side only marshals arguments.
+ *
+ * Semantics fixed by this library (the paper leaves them open):
+ *   - Snapshot sweeps: every token of a sweep reads the assignment z and all
+ *     counts as of the start of the sweep (the limit of the paper's immutable
+ *     model slice with delayed updates, Sec. 6 "Multi-thread Efficiency").
+ *     A token's own contribution is removed at its snapshot topic.
+ *   - One MH step is one proposal plus one accept test; step j of a token is a
+ *     word-proposal for even j and a doc-proposal for odd j (Eq. 13).
+ *   - Randomness is Philox4x32-10 with key = seed and counter
+ *     (token id low, token id high, sweep index, step index), so results do not
+ *     depend on launch geometry.  Acceptance ratios are evaluated in fp64 with
+ *     separately rounded operations.
+ *
+ * Conventions
+ *   - All pointers in the signatures are HOST pointers unless stated otherwise.
+ *     The library copies what it needs; the caller keeps ownership of its buffers
+ *     and may free them as soon as a call returns.
+ *   - Token order at the boundary is the caller's CSR (document-major) order:
+ *     token g is word_ids[g]; document d owns g in [doc_offsets[d], doc_offsets[d+1]).
+ *   - Return value 0 (LDA_OK) on success, a negative LDA_ERR_* otherwise; no call
+ *     throws.  lda_last_error() returns a message for the last failure.
+ *   - lda_build_alias, lda_sweep and lda_rebuild_counts enqueue work on the
+ *     context's HIP stream and return; accessors and lda_loglik synchronise.
+ *   - A context is not thread-safe.  Calls must follow the state machine
+ *       COUNTS_VALID --lda_build_alias--> ALIAS_VALID --lda_sweep--> SWEPT
+ *       SWEPT --lda_rebuild_counts--> COUNTS_VALID
+ *     and return LDA_ERR_STATE otherwise.
+ */
+#ifndef LDA_MI355X_H
+#define LDA_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LDA_OK 0
+#define LDA_ERR_ARG (-1)         /* bad pointer, size, id out of range, alpha/beta <= 0, ... */
+#define LDA_ERR_STATE (-2)       /* call out of order */
+#define LDA_ERR_OOM (-3)         /* host or device allocation failed */
+#define LDA_ERR_HIP (-4)         /* a HIP runtime call or kernel launch failed */
+#define LDA_ERR_UNSUPPORTED (-5) /* valid request outside what this build supports */
+
+typedef struct lda_ctx lda_ctx; /* opaque; owns all device memory of one corpus */
+
+/* Options for lda_init.  A zeroed struct (or a NULL pointer) selects the defaults. */
+typedef struct lda_options {
+    void* hip_stream;              /* hipStream_t all work is enqueued on; NULL: the null stream */
+    int32_t dense_rows;            /* number of most frequent word ids [0, dense_rows) whose n_kw row
+                                      is stored dense (hybrid store, Sec. 5); 0: every row dense */
+    int32_t dense_alias_min_count; /* words with corpus frequency >= this draw from a dense K-bin
+                                      table, the others from the sparsified mixture (Sec. 4.2);
+                                      0: every word uses the dense table */
+    int32_t proposal_mode;         /* 0: cycle word,doc,word,... (Eq. 13); 1: word only; 2: doc only */
+    int32_t sweep_chunk_tokens;    /* tuning: tokens per sweep workgroup tile; 0: default */
+    int32_t sweep_block_threads;   /* tuning: threads per sweep workgroup; 0: default */
+    int32_t rebuild_tile_tokens;   /* tuning: tokens per count-rebuild tile; 0: default */
+    int32_t reserved[9];           /* must be zero */
+} lda_options;
+
+/*
+ * lda_init -- take a corpus and set up the sampler state (problem statement: Sec. 3).
+ *   D            number of documents (>= 1); empty documents are legal
+ *   V, K         vocabulary size and number of topics (>= 1)
+ *   doc_offsets  [D+1] host, doc_offsets[0] = 0, non-decreasing, N = doc_offsets[D] in [1, 2^31-2]
+ *   word_ids     [N] host, each in [0, V)
+ *   alpha, beta  symmetric Dirichlet parameters (> 0) of Eq. (1)
+ *   seed         Philox key
+ * Copies the corpus to the device, builds the word-major token order and the
+ * document tiling, draws the initial assignment z[g] = floor(x0 * K / 2^32) from
+ * the Philox counter (g, 0xFFFFFFFF, 0) and counts n_kw, n_k.  On success
+ * *out is a new context in state COUNTS_VALID with sweep index 0.
+ */
+int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_offsets,
+             const int32_t* word_ids, double alpha, double beta, uint64_t seed,
+             const lda_options* opt);
+
+/*
+ * lda_build_alias -- word-proposal tables of Eq. (6) for every word, from the
+ * current counts: per topic bin a split point and an alias (Sec. 4.2, Fig. 2),
+ * plus the bin capacity of the word.  COUNTS_VALID -> ALIAS_VALID.
+ */
+int lda_build_alias(lda_ctx* ctx);
+
+/*
+ * lda_sweep -- one sweep: for every token mh_steps (>= 1) Metropolis-Hastings
+ * steps alternating the word-proposal (Eq. 6-8) and the doc-proposal
+ * (Eq. 9-12) against the conditional of Eq. (4), all reads from the snapshot.
+ * Uses the context's sweep index as Philox counter word 2 and increments it.
+ * ALIAS_VALID -> SWEPT (the counts no longer match z).
+ */
+int lda_sweep(lda_ctx* ctx, int32_t mh_steps);
+
+/*
+ * lda_rebuild_counts -- recount n_kw (per-word histogram of the word-major
+ * token segments) and n_k from the current assignment; the per-document counts
+ * n_kd are formed inside the sweep from the document's assignments.
+ * SWEPT (or any state) -> COUNTS_VALID.
+ */
+int lda_rebuild_counts(lda_ctx* ctx);
+
+/*
+ * lda_loglik -- log p(w, z | alpha, beta) of the collapsed model, the metric of
+ * Sec. 7 ("doc-likelihood" + "word-likelihood"); fp64.  Needs valid counts.
+ * doc_part / word_part may be NULL.  Synchronises.
+ */
+int lda_loglik(lda_ctx* ctx, double* total, double* doc_part, double* word_part);
+
+/* ---- accessors (parity checks, checkpoint / warm start of Sec. 6); all synchronise ---- */
+int64_t lda_num_tokens(const lda_ctx* ctx);
+int64_t lda_sweep_index(const lda_ctx* ctx);
+/* z [N] in CSR token order. */
+int lda_get_z(lda_ctx* ctx, int32_t* z);
+/* Replace the assignment (each z[g] in [0,K)) and the next sweep index (< 2^32-1); -> SWEPT. */
+int lda_set_z(lda_ctx* ctx, const int32_t* z, int64_t next_sweep_index);
+/* nk [K]; needs valid counts. */
+int lda_get_nk(lda_ctx* ctx, int32_t* nk);
+/* Dense copy of row w of the word-topic table, row [K]; needs valid counts. */
+int lda_get_nkw_row(lda_ctx* ctx, int32_t w, int32_t* row);
+/* Dense copy of row d of the doc-topic table as the sweep kernel forms it, row [K]. */
+int lda_get_ndk_row(lda_ctx* ctx, int64_t d, int32_t* row);
+/* Dense-form table of word w: split [K], alias [K], *cap = bin capacity; needs ALIAS_VALID. */
+int lda_get_alias_row(lda_ctx* ctx, int32_t w, uint32_t* split, uint32_t* alias, uint32_t* cap);
+
+/* Wait for all work enqueued by this context. */
+int lda_sync(lda_ctx* ctx);
+/* Message of the last error of this context (ctx == NULL: of the last failed lda_init on this
+ * thread).  The string is owned by the library and valid until the next call. */
+const char* lda_last_error(const lda_ctx* ctx);
+/* Free the context and all its device memory.  NULL is allowed. */
+void lda_destroy(lda_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LDA_MI355X_H */

@@ -1,0 +1,138 @@
+// Shared declarations of the gfx950 LightLDA library: context, launch helpers,
+// and the small device routines every kernel uses (Philox4x32-10, mulhi).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/lda_mi355x.h"
+
+namespace lda {
+
+constexpr int kWave = 64;
+
+enum State { COUNTS_VALID = 1, ALIAS_VALID = 2, SWEPT = 3 };
+
+// One rebuild work item: a slice [p0, p1) of word w's word-major segment.
+struct RebuildTile {
+    int32_t w;
+    int32_t p0;
+    int32_t p1;
+    int32_t multi;  // 1: the word has several tiles (row pre-zeroed, merged by atomics)
+};
+
+}  // namespace lda
+
+struct lda_ctx {
+    // problem
+    int64_t D = 0, N = 0;
+    int32_t V = 0, K = 0;
+    double alpha = 0, beta = 0, alphabar = 0, betabar = 0;
+    uint64_t seed = 0;
+    lda_options opt{};
+    hipStream_t stream = nullptr;
+    int state = 0;
+    uint32_t sweep_index = 0;
+    std::string err;
+
+    // corpus, document-major (CSR order)
+    int32_t* d_word = nullptr;  // [N] word id of token g
+    int32_t* d_doff = nullptr;  // [D+1] token offset of document d
+    int32_t* d_z = nullptr;     // [N] snapshot assignment
+    int32_t* d_znew = nullptr;  // [N] next assignment
+    // word-major view
+    int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order
+    int32_t* d_woff = nullptr;  // [V+1] segment offsets
+    // model
+    int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)
+    int32_t* d_nk = nullptr;    // [K]
+    uint2* d_alias = nullptr;   // [V*K] (split, alias) per bin
+    uint32_t* d_cap = nullptr;  // [V] bin capacity of the word's table
+    // sweep tiling: chunk c covers documents [chunk_doc[c], chunk_doc[c+1])
+    int32_t* d_chunk_doc = nullptr;
+    int32_t n_chunks = 0;
+    int32_t chunk_tokens = 0, chunk_docs = 0, sweep_block = 0;
+    // documents too long for an LDS tile: hashed in a global workspace
+    int32_t* d_long_doc = nullptr;     // [n_long] document ids
+    int64_t* d_long_slot = nullptr;    // [n_long+1] first hash slot of each long document
+    int32_t* d_long_keys = nullptr;    // [total slots]
+    int32_t* d_long_cnts = nullptr;
+    int32_t n_long = 0;
+    int64_t long_slots = 0;
+    std::vector<int32_t> h_long_doc;
+    // rebuild tiling
+    lda::RebuildTile* d_tiles = nullptr;
+    int32_t n_tiles = 0;
+    int32_t* d_multi_words = nullptr;  // words that own several tiles
+    int32_t n_multi_words = 0;
+    // scratch
+    double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
+    int32_t n_partial = 0;
+    int32_t* d_row = nullptr;          // [max(K,1)] row staging for accessors
+    int32_t* d_flag = nullptr;         // [4] validation flags
+    // host copies of small layouts
+    std::vector<int32_t> h_doff;
+};
+
+namespace lda {
+
+int fail(lda_ctx* c, int code, const char* fmt, ...);
+void set_init_error(const char* msg);
+
+#define LDA_HIP(ctx, call)                                                              \
+    do {                                                                                \
+        hipError_t e__ = (call);                                                        \
+        if (e__ != hipSuccess)                                                          \
+            return lda::fail((ctx), e__ == hipErrorOutOfMemory ? LDA_ERR_OOM : LDA_ERR_HIP, \
+                             "%s: %s (%s:%d)", #call, hipGetErrorString(e__), __FILE__, __LINE__); \
+    } while (0)
+
+// launchers implemented in the kernel files
+int launch_layout(lda_ctx* c, const int32_t* h_word);      // word-major order, woff, z init
+int launch_alias_build(lda_ctx* c);
+int launch_sweep(lda_ctx* c, int32_t mh_steps);
+int launch_rebuild(lda_ctx* c);
+int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
+int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
+int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo, int32_t hi,
+                       bool* ok);
+int max_alias_topics();    // largest K the dense alias kernel handles
+int max_rebuild_topics();  // largest K the count-rebuild tiles handle
+
+// ------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t mulhi32(uint32_t a, uint32_t b) { return __umulhi(a, b); }
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies,
+// the key advanced by Weyl constants between rounds.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        if (r > 0) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// (x + 1/2) / 2^32: uniform in (0,1), exact in fp64
+__device__ __forceinline__ double unit_open(uint32_t x)
+{
+    return ((double)x + 0.5) * (1.0 / 4294967296.0);
+}
+
+}  // namespace lda

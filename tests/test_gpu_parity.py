@@ -1,0 +1,200 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Integer results (z, n_k, n_kw, n_dk, alias tables) must be bit-identical;
+the log-likelihood must agree to 1e-9 relative.
+"""
+import numpy as np
+import pytest
+
+from paper_1412_1576_amd import corpus
+
+pytestmark = pytest.mark.gpu
+
+LOGLIK_RTOL = 1e-9
+
+
+@pytest.fixture(scope="module")
+def lda_mod():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1412_1576_amd import lda
+    lda.load_library()
+    return lda
+
+
+def check_state(g, o, docs=(), words=None, alias_words=None, tag=""):
+    """Compare every observable of the two contexts (both with valid counts)."""
+    zg, zo = g.get_z(), o.get_z()
+    assert np.array_equal(zg, zo), "%s z differs at %d tokens" % (tag, int((zg != zo).sum()))
+    assert np.array_equal(g.get_nk(), o.get_nk()), tag + " n_k"
+    assert int(g.get_nk().sum()) == g.N
+    ws = range(g.V) if words is None else words
+    for w in ws:
+        assert np.array_equal(g.get_nkw_row(w), o.get_nkw_row(w)), "%s n_kw row %d" % (tag, w)
+    for d in docs:
+        assert np.array_equal(g.get_ndk_row(d), o.get_ndk_row(d)), "%s n_dk row %d" % (tag, d)
+    tg, dg, wg = g.loglik()
+    to, do, wo = o.loglik()
+    assert abs(dg - do) <= LOGLIK_RTOL * abs(do), (tag, dg, do)
+    assert abs(wg - wo) <= LOGLIK_RTOL * abs(wo), (tag, wg, wo)
+    assert abs(tg - to) <= LOGLIK_RTOL * abs(to), (tag, tg, to)
+
+
+def check_alias(g, o, words, tag=""):
+    for w in words:
+        sg, ag, cg = g.get_alias_row(w)
+        so, ao, co = o.get_alias_row(w)
+        assert cg == co, "%s alias capacity of word %d" % (tag, w)
+        assert np.array_equal(sg, so), "%s alias split of word %d" % (tag, w)
+        assert np.array_equal(ag, ao), "%s alias index of word %d" % (tag, w)
+
+
+def run_pair(lda_mod, oracle_mod, doff, words, V, K, alpha, beta, seed, sweeps, mh_steps,
+             docs=(), nkw_words=None, alias_words=None, **opt):
+    g = lda_mod.Lda(doff, words, V, K, alpha, beta, seed=seed, **opt)
+    o = oracle_mod.Oracle(doff, words, V, K, alpha, beta, seed=seed,
+                          proposal_mode=opt.get("proposal_mode", 0))
+    check_state(g, o, docs, nkw_words, tag="init")
+    for it in range(sweeps):
+        g.build_alias()
+        o.build_alias()
+        check_alias(g, o, range(V) if alias_words is None else alias_words, tag="sweep %d" % it)
+        g.sweep(mh_steps)
+        o.sweep(mh_steps)
+        g.rebuild_counts()
+        o.rebuild_counts()
+        check_state(g, o, docs, nkw_words, tag="sweep %d" % it)
+    assert g.sweep_index == o.sweep_index == sweeps
+    g.close()
+    o.close()
+
+
+def test_c1_full_parity_every_sweep(lda_mod, oracle_mod):
+    cfg = corpus.CONFIGS["c1"]
+    doff, words = corpus.make_corpus(cfg)
+    run_pair(lda_mod, oracle_mod, doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, cfg.lib_seed,
+             cfg.sweeps, cfg.mh_steps, docs=range(0, cfg.D, 37))
+
+
+def ragged_corpus(V, seed=3, long_len=700):
+    """Empty documents (also first and last), one-token documents, a long one."""
+    rng = np.random.default_rng(seed)
+    lens = [0, 0, 1, 5, 0, long_len, 1, 1, 17, 0, 64, 63, 65, 128, 2, 0, 300, 0]
+    lens += list(rng.integers(0, 40, 150))
+    lens += [0, 0]
+    doff = np.zeros(len(lens) + 1, np.int64)
+    doff[1:] = np.cumsum(lens)
+    p = 1.0 / np.arange(1, V + 1)
+    words = rng.choice(V, int(doff[-1]), p=p / p.sum()).astype(np.int32)
+    return doff, words
+
+
+@pytest.mark.parametrize("K", [1, 2, 7, 64, 65, 100])
+def test_ragged_documents_and_small_K(lda_mod, oracle_mod, K):
+    V = 50
+    doff, words = ragged_corpus(V)
+    D = len(doff) - 1
+    # tiles of 128 tokens: documents 5, 13 (=128, fits), 16 are "long" or boundary cases
+    run_pair(lda_mod, oracle_mod, doff, words, V, K, 0.1, 0.05, 77, 3, 3, docs=range(D),
+             sweep_chunk_tokens=128, sweep_block_threads=64, rebuild_tile_tokens=64)
+
+
+def test_long_documents_default_tiles(lda_mod, oracle_mod):
+    V = 300
+    doff, words = ragged_corpus(V, seed=4, long_len=9000)
+    run_pair(lda_mod, oracle_mod, doff, words, V, 40, 0.2, 0.01, 5, 2, 4,
+             docs=[0, 2, 5, 13, 16, len(doff) - 2])
+
+
+def test_single_word_vocabulary(lda_mod, oracle_mod):
+    doff = np.array([0, 3, 3, 10], np.int64)
+    words = np.zeros(10, np.int32)
+    run_pair(lda_mod, oracle_mod, doff, words, 1, 5, 0.5, 0.5, 1, 3, 2, docs=range(3))
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_proposal_modes(lda_mod, oracle_mod, mode):
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=200)
+    doff, words = corpus.make_corpus(cfg)
+    run_pair(lda_mod, oracle_mod, doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, 3, 2, 3,
+             docs=range(0, 200, 11), proposal_mode=mode)
+
+
+@pytest.mark.parametrize("K,mh", [(1000, 2), (1024, 1), (1025, 2), (2500, 2), (4096, 3),
+                                  (10000, 4), (12288, 2)])
+def test_larger_K_alias_paths(lda_mod, oracle_mod, K, mh):
+    """Every bins-per-thread variant of the alias build, rows with few and many non-zeros."""
+    cfg = corpus.scaled(corpus.CONFIGS["c2"], D=400, V=600, K=K, alpha=50.0 / K)
+    doff, words = corpus.make_corpus(cfg)
+    run_pair(lda_mod, oracle_mod, doff, words, cfg.V, K, cfg.alpha, cfg.beta, 11, 2, mh,
+             docs=range(0, 400, 41), nkw_words=range(0, 600, 7), alias_words=range(0, 600, 5))
+
+
+def test_medium_shape_parity(lda_mod, oracle_mod):
+    """C2-shaped (K = 1000) at 1/100 of the documents: several sweeps, hot words spanning
+    many rebuild tiles."""
+    cfg = corpus.scaled(corpus.CONFIGS["c2"], D=3000)
+    doff, words = corpus.make_corpus(cfg)
+    run_pair(lda_mod, oracle_mod, doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, 0, 3, 2,
+             docs=range(0, 3000, 211), nkw_words=list(range(0, 50)) + list(range(50, cfg.V, 997)),
+             alias_words=list(range(0, 20)) + list(range(20, cfg.V, 1999)),
+             rebuild_tile_tokens=4096)
+
+
+def test_launch_geometry_does_not_change_results(lda_mod):
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=300)
+    doff, words = corpus.make_corpus(cfg)
+    outs = []
+    for opt in (dict(), dict(sweep_chunk_tokens=256, sweep_block_threads=128),
+                dict(sweep_chunk_tokens=4096, sweep_block_threads=1024, rebuild_tile_tokens=100)):
+        g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=9, **opt)
+        for it in range(3):
+            g.build_alias(); g.sweep(2); g.rebuild_counts()
+        outs.append((g.get_z(), g.get_nk()))
+        g.close()
+    for z, nk in outs[1:]:
+        assert np.array_equal(z, outs[0][0]) and np.array_equal(nk, outs[0][1])
+
+
+def test_state_machine_and_checkpoint(lda_mod, oracle_mod):
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=150)
+    doff, words = corpus.make_corpus(cfg)
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=2)
+    with pytest.raises(lda_mod.LdaError) as e:
+        g.sweep(2)                       # no alias tables yet
+    assert e.value.code == lda_mod.LDA_ERR_STATE
+    g.build_alias()
+    with pytest.raises(lda_mod.LdaError):
+        g.sweep(0)
+    g.sweep(2)
+    with pytest.raises(lda_mod.LdaError) as e:
+        g.sweep(2)                       # stale tables are refused
+    assert e.value.code == lda_mod.LDA_ERR_STATE
+    with pytest.raises(lda_mod.LdaError):
+        g.get_nk()                       # counts are stale
+    with pytest.raises(lda_mod.LdaError):
+        g.build_alias()
+    g.rebuild_counts()
+    saved, idx = g.get_z(), g.sweep_index
+    for it in range(2):
+        g.build_alias(); g.sweep(2); g.rebuild_counts()
+    ref = g.get_z()
+    # warm start in a fresh context
+    h = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=2)
+    bad = saved.copy()
+    bad[5] = cfg.K
+    with pytest.raises(lda_mod.LdaError) as e:
+        h.set_z(bad, idx)
+    assert e.value.code == lda_mod.LDA_ERR_ARG
+    h.set_z(saved, idx)
+    h.rebuild_counts()
+    for it in range(2):
+        h.build_alias(); h.sweep(2); h.rebuild_counts()
+    assert np.array_equal(h.get_z(), ref)
+    # out-of-range word id is caught by the device-side check
+    w2 = words.copy()
+    w2[7] = cfg.V
+    with pytest.raises(lda_mod.LdaError) as e:
+        lda_mod.Lda(doff, w2, cfg.V, cfg.K, cfg.alpha, cfg.beta)
+    assert e.value.code == lda_mod.LDA_ERR_ARG
+    g.close(); h.close()
