@@ -63,6 +63,10 @@ def load_library():
         raise ImportError(
             "%s not found: build it with `python -m paper_1412_1576_amd.build`; "
             "there is no CPU fallback" % LIB_PATH)
+    # PyTorch supplies device memory and streams to callers and ships its own HIP
+    # runtime; import it first so that this library binds to the runtime the
+    # process already uses (two HIP/HSA runtimes in one process cannot share the GPU).
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp = C.c_void_p
     dp = C.POINTER(C.c_double)
