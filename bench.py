@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the MI355X LightLDA hot path: tokens/s of whole iterations
+(alias build + cycle-MH sweep + count rebuild) on a synthetic Zipf corpus,
+the sweep kernel's roofline figures, and the CPU oracle timed beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c1] [--mh-steps M]
+
+Prints ONE JSON line.  One GPU only: --gpus N with N > 1 exits with a message.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes_per_token(mh_steps: int) -> float:
+    """Bytes the method touches per token per sweep, counted operand by operand
+    (no reuse assumed): token stream 16 B (doc id, position, z in, z out), document
+    header 8 B, state at the snapshot topic 16 B (n_kw, n_k, n_kd probe), each word
+    step 24 B (alias bin 8, n_kw 4, n_k 4, n_kd probe 8), each doc step 20 B
+    (z of a random token 4, n_kw 4, n_k 4, n_kd probe 8): 40 + 22 m for m steps."""
+    return 40.0 + 22.0 * mh_steps
+
+
+def design_bytes_per_token(mh_steps: int) -> float:
+    """What this design has to bring from HBM per token: the stream (word id,
+    z in, z out: 12 B; the document side is then served from LDS), n_kw and n_k at
+    the snapshot topic (8 B), per word step an alias bin + n_kw + n_k (16 B), per
+    doc step n_kw + n_k (8 B)."""
+    word_steps = (mh_steps + 1) // 2
+    doc_steps = mh_steps // 2
+    return 12.0 + 8.0 + 16.0 * word_steps + 8.0 * doc_steps
+
+
+# HBM bytes per sweep launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); keyed by (workload, mh_steps).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(cfg, doff, words, mh_steps, sample_docs):
+    """The oracle as it stands on the first `sample_docs` documents (same V, K)."""
+    import oracle
+    D = min(sample_docs, len(doff) - 1)
+    sdoff = np.ascontiguousarray(doff[: D + 1])
+    swords = np.ascontiguousarray(words[: int(sdoff[-1])])
+    o = oracle.Oracle(sdoff, swords, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                      lazy_alias=True)
+    t0 = time.perf_counter()
+    o.build_alias()
+    o.sweep(mh_steps)
+    o.rebuild_counts()
+    dt = time.perf_counter() - t0
+    n = o.N
+    o.close()
+    return {
+        "value": n / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "sample": "first %d documents (%d tokens) of the same corpus, same V and K; one full "
+                  "iteration (alias tables of the words that occur, sweep, recount), %.1f s"
+                  % (D, n, dt),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--mh-steps", type=int, default=2)
+    ap.add_argument("--docs", type=int, default=0, help="use only the first DOCS documents' worth "
+                    "of the workload (debugging; the result is then not the headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-docs", type=int, default=0)
+    ap.add_argument("--chunk-tokens", type=int, default=0)
+    ap.add_argument("--block-threads", type=int, default=0)
+    ap.add_argument("--tile-tokens", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a "
+              "design note, not code", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1412_1576_amd import corpus, lda
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+
+    cfg = corpus.CONFIGS[args.workload]
+    if args.docs:
+        cfg = corpus.scaled(cfg, D=args.docs)
+    t0 = time.perf_counter()
+    doff, words = corpus.make_corpus(cfg)
+    t_gen = time.perf_counter() - t0
+    N = int(doff[-1])
+
+    stream = torch.cuda.Stream()
+    t0 = time.perf_counter()
+    g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                stream=stream.cuda_stream, sweep_chunk_tokens=args.chunk_tokens,
+                sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens)
+    g.sync()
+    t_init = time.perf_counter() - t0
+
+    def iteration(evs=None):
+        if evs:
+            evs[0].record(stream)
+        g.build_alias()
+        if evs:
+            evs[1].record(stream)
+        g.sweep(args.mh_steps)
+        if evs:
+            evs[2].record(stream)
+        g.rebuild_counts()
+        if evs:
+            evs[3].record(stream)
+
+    for _ in range(args.warmup):
+        iteration()
+    g.sync()
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    start.record(stream)
+    for s in range(args.steps):
+        iteration(evs[s])
+    stop.record(stream)
+    g.sync()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    total_ms = start.elapsed_time(stop)
+    alias_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    sweep_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    rebuild_ms = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    loglik = g.loglik()[0]
+    nk = g.get_nk()
+    assert int(nk.sum()) == N, "count invariant violated"
+
+    ms_per_step = total_ms / args.steps
+    abytes = algorithmic_bytes_per_token(args.mh_steps)
+    achieved = abytes * N / (sweep_ms * 1e-3) / 1e9
+    out = {
+        "metric": "sampled tokens/sec (alias build + %d-step MH sweep + count rebuild)" % args.mh_steps,
+        "value": N / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32 counts, fp64 acceptance",
+        "data": "synthetic",
+        "config": {
+            "workload": "%s: D=%d docs, N=%d tokens, V=%d Zipf(%.2f), K=%d, alpha=%g, beta=%g, "
+                        "mh_steps=%d, dense n_kw" % (cfg.name, cfg.D, N, cfg.V, cfg.s, cfg.K,
+                                                     cfg.alpha, cfg.beta, args.mh_steps),
+            "sweep_tokens_per_s": N / (sweep_ms * 1e-3),
+            "alias_ms": alias_ms, "sweep_ms": sweep_ms, "rebuild_ms": rebuild_ms,
+            "wall_s_timed_region": wall, "corpus_gen_s": t_gen, "init_s": t_init,
+            "loglik_after": loglik,
+        },
+        "roofline": {
+            "bound": "hbm", "kernel": "sweep_tiles_kernel",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS,
+            "algorithmic_bytes_per_token": abytes,
+            "design_bytes_per_token": design_bytes_per_token(args.mh_steps),
+            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name if not args.docs else None,
+                                                   args.mh_steps)),
+        },
+    }
+    g.close()
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 3000, "c3": 30000}[args.workload]
+        out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
