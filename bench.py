@@ -82,6 +82,8 @@ def main():
                     "of the workload (debugging; the result is then not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-docs", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true", help="also launch a plain "
+                    "elementwise kernel that reads 1 GiB and writes 1 GiB (scale for HBM counters)")
     ap.add_argument("--chunk-tokens", type=int, default=0)
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
@@ -129,6 +131,13 @@ def main():
         iteration()
     g.sync()
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)   # one kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     start = torch.cuda.Event(enable_timing=True)
