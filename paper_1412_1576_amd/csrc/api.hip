@@ -53,7 +53,7 @@ void free_all(lda_ctx* c)
 {
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
     dev_free(c->d_gid); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
-    dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_long_doc);
+    dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
     dev_free(c->d_flag);
@@ -128,6 +128,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (o.dense_rows != 0 || o.dense_alias_min_count != 0)
         return fail(nullptr, LDA_ERR_UNSUPPORTED,
                     "lda_init: hybrid rows / mixture proposal are not available in this build");
+    if (K > kMaxPackedTopics)
+        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K must be < 2^20");
     if (K > max_alias_topics() || K > max_rebuild_topics())
         return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K = %d exceeds the dense-path limit %d",
                     K, std::min(max_alias_topics(), max_rebuild_topics()));
@@ -144,12 +146,15 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     c->opt = o;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
 
-    // sweep tiling parameters (LDS: 20 bytes per token + 4 per document)
-    c->chunk_tokens = o.sweep_chunk_tokens > 0 ? o.sweep_chunk_tokens : 2048;
-    c->chunk_tokens = std::max(64, std::min(c->chunk_tokens, 7168));
-    c->chunk_docs = std::max(16, c->chunk_tokens / 4);
-    c->sweep_block = o.sweep_block_threads > 0 ? o.sweep_block_threads : 512;
+    // sweep tiling parameters (LDS: 12 bytes per token + 4 per document).  A packed n_kd
+    // slot holds counts up to 4095 and a one-byte document index, which bound the tile.
+    c->chunk_tokens = o.sweep_chunk_tokens > 0 ? o.sweep_chunk_tokens : 512;
+    c->chunk_tokens = std::max(64, std::min((c->chunk_tokens / 64) * 64, 4032));
+    c->chunk_docs = std::max(16, std::min(255, c->chunk_tokens / 4));
+    c->sweep_block = o.sweep_block_threads > 0 ? o.sweep_block_threads : 256;
     c->sweep_block = std::max(64, std::min(1024, (c->sweep_block / 64) * 64));
+    // a thread carries at most 8 tokens of its tile
+    c->sweep_block = std::max(c->sweep_block, ((c->chunk_tokens + 7) / 8 + 63) / 64 * 64);
     const int32_t tile_tokens = o.rebuild_tile_tokens > 0 ? o.rebuild_tile_tokens : 262144;
 
     int rc = LDA_OK;
@@ -198,6 +203,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_alias, VK, "alias tables"));
     TRY(dev_alloc(c, &c->d_cap, (size_t)V, "alias capacities"));
     TRY(dev_alloc(c, &c->d_chunk_doc, chunk_doc.size(), "document tiles"));
+    TRY(dev_alloc(c, &c->d_tokdoc, (size_t)N, "token document indices"));
     TRY(dev_alloc(c, &c->d_long_doc, (size_t)c->n_long, "long documents"));
     TRY(dev_alloc(c, &c->d_long_slot, (size_t)c->n_long + 1, "long document slots"));
     TRY(dev_alloc(c, &c->d_long_keys, (size_t)c->long_slots, "long document tables"));
@@ -225,6 +231,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (!ok) return bail(fail(nullptr, LDA_ERR_ARG, "lda_init: a word id is outside [0, V)"));
 
     TRY(launch_layout(c, word_ids));
+    TRY(launch_tokdoc(c));
 
     // rebuild tiles from the word segment offsets
     std::vector<int32_t> woff((size_t)V + 1);
@@ -383,9 +390,9 @@ int lda_get_alias_row(lda_ctx* c, int32_t w, uint32_t* split, uint32_t* alias, u
     if (!split || !alias || !cap || w < 0 || w >= c->V)
         return fail(c, LDA_ERR_ARG, "lda_get_alias_row: bad argument");
     if (c->state != ALIAS_VALID) return fail(c, LDA_ERR_STATE, "lda_get_alias_row: no valid tables");
-    std::vector<uint2> h((size_t)c->K);
+    std::vector<uint4> h((size_t)c->K);
     LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_alias + (size_t)w * (size_t)c->K,
-                              sizeof(uint2) * (size_t)c->K, hipMemcpyDeviceToHost, c->stream));
+                              sizeof(uint4) * (size_t)c->K, hipMemcpyDeviceToHost, c->stream));
     LDA_HIP(c, hipMemcpyAsync(cap, c->d_cap + w, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream));
     LDA_HIP(c, hipStreamSynchronize(c->stream));
     for (int32_t k = 0; k < c->K; ++k) {

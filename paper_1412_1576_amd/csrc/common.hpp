@@ -51,10 +51,11 @@ struct lda_ctx {
     // model
     int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)
     int32_t* d_nk = nullptr;    // [K]
-    uint2* d_alias = nullptr;   // [V*K] (split, alias) per bin
+    uint4* d_alias = nullptr;   // [V*K] (split, alias, n_kw[bin], n_kw[alias]) per bin
     uint32_t* d_cap = nullptr;  // [V] bin capacity of the word's table
     // sweep tiling: chunk c covers documents [chunk_doc[c], chunk_doc[c+1])
     int32_t* d_chunk_doc = nullptr;
+    uint8_t* d_tokdoc = nullptr;     // [N] index of the token's document inside its tile
     int32_t n_chunks = 0;
     int32_t chunk_tokens = 0, chunk_docs = 0, sweep_block = 0;
     // documents too long for an LDS tile: hashed in a global workspace
@@ -96,6 +97,7 @@ void set_init_error(const char* msg);
 int launch_layout(lda_ctx* c, const int32_t* h_word);      // word-major order, woff, z init
 int launch_alias_build(lda_ctx* c);
 int launch_sweep(lda_ctx* c, int32_t mh_steps);
+int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
 int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
@@ -120,11 +122,15 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
             k0 += 0x9E3779B9u;
             k1 += 0xBB67AE85u;
         }
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        const uint32_t n0 = hi1 ^ c1 ^ k0;
-        const uint32_t n2 = hi0 ^ c3 ^ k1;
-        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        // full 64-bit products: one multiply instruction yields both halves
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
     }
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }

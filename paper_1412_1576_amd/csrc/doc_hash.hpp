@@ -1,10 +1,11 @@
 // Per-document topic counts n_kd as a small open-addressing hash table.
 //
 // The doc-topic row of a document with L tokens has at most L non-zeros, so it
-// is kept as 2L (topic, count) slots (load factor <= 1/2), built from the
-// document's assignments when a workgroup picks the document up.  Short
-// documents live in LDS next to the document's z values; documents too long for
-// an LDS tile use the same code on a global-memory workspace.
+// is kept in 2L slots (load factor <= 1/2), built from the document's
+// assignments when a workgroup picks the document up.  Documents that fit an LDS
+// tile pack (count << 20 | topic) into one 32-bit slot next to the document's z
+// values; documents too long for a tile keep (topic, count) in two arrays of a
+// global-memory workspace.
 #pragma once
 
 #include "common.hpp"
@@ -12,24 +13,68 @@
 namespace lda {
 
 constexpr int32_t kEmptyKey = -1;
+constexpr uint32_t kEmptySlot = 0xFFFFFFFFu;
+constexpr int kTopicBits = 20;                       // packed slots: topic < 2^20 - 1
+constexpr uint32_t kTopicMask = (1u << kTopicBits) - 1u;
+constexpr int32_t kMaxPackedTopics = (1 << kTopicBits) - 1;
+constexpr int32_t kMaxPackedCount = (1 << (32 - kTopicBits)) - 1;  // 4095 tokens per document
+
+// Slot of topic k in a table of `slots` < 2^16 entries.  Both multiplies are
+// 24-bit (full rate on the vector ALU): a 16-bit golden-ratio multiplier spreads
+// k, the middle 16 bits of the product are scaled to [0, slots).
+__device__ __forceinline__ uint32_t packed_slot(int32_t k, uint32_t slots)
+{
+    const uint32_t h = (__umul24((uint32_t)k, 40503u) >> 4) & 0xFFFFu;
+    return __umul24(h, slots) >> 16;
+}
+
+// LDS table of one document.
+struct PackedDocTable {
+    uint32_t* tab;
+    uint32_t slots;  // 2 * L, 2 <= slots <= 8190
+
+    __device__ __forceinline__ void insert(int32_t k) const
+    {
+        uint32_t s = packed_slot(k, slots);
+        for (uint32_t n = 0; n < slots; ++n) {
+            const uint32_t prev = atomicCAS(&tab[s], kEmptySlot, (1u << kTopicBits) | (uint32_t)k);
+            if (prev == kEmptySlot) return;
+            if ((prev & kTopicMask) == (uint32_t)k) {
+                atomicAdd(&tab[s], 1u << kTopicBits);
+                return;
+            }
+            s = (s + 1 == slots) ? 0u : s + 1;
+        }
+    }
+
+    // n_kd of topic k (0 when the document has no token of it).  An empty slot
+    // always exists because the load factor is <= 1/2.
+    __device__ __forceinline__ int32_t count(int32_t k) const
+    {
+        uint32_t s = packed_slot(k, slots);
+        for (uint32_t n = 0; n < slots; ++n) {
+            const uint32_t v = tab[s];
+            if ((v & kTopicMask) == (uint32_t)k) return (int32_t)(v >> kTopicBits);
+            if (v == kEmptySlot) return 0;
+            s = (s + 1 == slots) ? 0u : s + 1;
+        }
+        return 0;
+    }
+};
 
 __device__ __forceinline__ uint32_t topic_hash(int32_t k) { return (uint32_t)k * 0x9E3779B1u; }
 
-// GLOBAL = false: keys/cnts point into LDS.  GLOBAL = true: they point into
-// device memory that other lanes of the workgroup update with atomics, so reads
-// go through agent-scope atomic loads (they must not be served from a stale L1 line).
-template <bool GLOBAL>
-struct DocTable {
+// Global-memory table of one long document.  Other lanes of the workgroup update
+// it with atomics, so reads go through agent-scope atomic loads (they must not be
+// served from a stale L1 line).
+struct GlobalDocTable {
     int32_t* keys;
     int32_t* cnts;
-    uint32_t slots;  // 2 * L >= 2
+    uint32_t slots;  // 2 * L
 
     __device__ __forceinline__ static int32_t ld(const int32_t* p)
     {
-        if constexpr (GLOBAL)
-            return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        else
-            return *p;
+        return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     __device__ __forceinline__ void insert(int32_t k) const
@@ -45,8 +90,6 @@ struct DocTable {
         }
     }
 
-    // n_kd of topic k (0 when the document has no token of it).  At most `slots`
-    // probes; an empty slot always exists because the load factor is <= 1/2.
     __device__ __forceinline__ int32_t count(int32_t k) const
     {
         uint32_t s = mulhi32(topic_hash(k), slots);
@@ -61,7 +104,7 @@ struct DocTable {
 };
 
 // Index of the document that owns local token i: the last dl with sdoff[dl] <= i,
-// where sdoff[0..nd] are the chunk-relative document offsets (sdoff[nd] > i).
+// where sdoff[0..nd] are the tile-relative document offsets (sdoff[nd] > i).
 __device__ __forceinline__ int32_t find_doc(const int32_t* sdoff, int32_t nd, int32_t i)
 {
     int32_t lo = 0, hi = nd;  // sdoff[lo] <= i < sdoff[hi]

@@ -28,8 +28,9 @@ __device__ __forceinline__ double block_sum_f64(double v, double* wtot)
 // doc part over LDS document tiles: one partial per tile
 __global__ __launch_bounds__(1024) void loglik_doc_tiles_kernel(
     const int32_t* __restrict__ z, const int32_t* __restrict__ doff,
-    const int32_t* __restrict__ chunk_doc, int32_t cap_tokens, double alpha, double alphabar,
-    double lg_alpha, double lg_alphabar, double* __restrict__ partial)
+    const int32_t* __restrict__ chunk_doc, const uint8_t* __restrict__ tokdoc, int32_t cap_tokens,
+    double alpha, double alphabar, double lg_alpha, double lg_alphabar,
+    double* __restrict__ partial)
 {
     extern __shared__ int32_t smem[];
     __shared__ double wtot[16];
@@ -37,11 +38,13 @@ __global__ __launch_bounds__(1024) void loglik_doc_tiles_kernel(
     const int32_t d0 = chunk_doc[c], d1 = chunk_doc[c + 1];
     double acc = 0.0;
     if (doff[d1] - doff[d0] <= cap_tokens) {
-        const DocTile T = load_doc_tile(smem, cap_tokens, z, doff, d0, d1);
+        const DocTile T = load_doc_tile(smem, cap_tokens, z, doff, tokdoc, d0, d1);
         for (int32_t i = threadIdx.x; i < T.nd; i += blockDim.x)
             acc += lg_alphabar - lgamma((double)(T.sdoff[i + 1] - T.sdoff[i]) + alphabar);
-        for (int32_t i = threadIdx.x; i < 2 * T.ntok; i += blockDim.x)
-            if (T.hkey[i] != kEmptyKey) acc += lgamma((double)T.hcnt[i] + alpha) - lg_alpha;
+        for (int32_t i = threadIdx.x; i < 2 * T.ntok; i += blockDim.x) {
+            const uint32_t v = T.tab[i];
+            if (v != kEmptySlot) acc += lgamma((double)(v >> kTopicBits) + alpha) - lg_alpha;
+        }
     }
     const double s = block_sum_f64(acc, wtot);
     if (threadIdx.x == 0) partial[c] = s;
@@ -58,12 +61,12 @@ __global__ __launch_bounds__(1024) void loglik_long_docs_kernel(
     const int32_t tok0 = doff[d];
     const int32_t L = doff[d + 1] - tok0;
     const int64_t s0 = long_slot[blockIdx.x];
-    const DocTable<true> tab = load_long_doc(keys + s0, cnts + s0, z + tok0, L);
+    const GlobalDocTable tab = load_long_doc(keys + s0, cnts + s0, z + tok0, L);
     double acc = 0.0;
     if (threadIdx.x == 0) acc += lg_alphabar - lgamma((double)L + alphabar);
     for (uint32_t i = threadIdx.x; i < tab.slots; i += blockDim.x)
-        if (DocTable<true>::ld(&tab.keys[i]) != kEmptyKey)
-            acc += lgamma((double)DocTable<true>::ld(&tab.cnts[i]) + alpha) - lg_alpha;
+        if (GlobalDocTable::ld(&tab.keys[i]) != kEmptyKey)
+            acc += lgamma((double)GlobalDocTable::ld(&tab.cnts[i]) + alpha) - lg_alpha;
     const double s = block_sum_f64(acc, wtot);
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
@@ -124,8 +127,8 @@ int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
             LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(loglik_doc_tiles_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(loglik_doc_tiles_kernel, dim3(c->n_chunks), dim3(c->sweep_block), lds,
-                           c->stream, c->d_z, c->d_doff, c->d_chunk_doc, c->chunk_tokens, c->alpha,
-                           c->alphabar, lga, lgab, c->d_partial);
+                           c->stream, c->d_z, c->d_doff, c->d_chunk_doc, c->d_tokdoc, c->chunk_tokens,
+                           c->alpha, c->alphabar, lga, lgab, c->d_partial);
         LDA_HIP(c, hipGetLastError());
         LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * c->n_chunks,
                                   hipMemcpyDeviceToHost, c->stream));

@@ -6,6 +6,8 @@
 // random token of the document" (Eq. 12) and the n_kd factors of the ratios --
 // is served from LDS.  The word side (alias bin, n_kw, n_k) is gathered from
 // HBM/L2.  Every token runs its mh_steps fused in registers and writes one int.
+// An alias bin carries the word-topic counts of its two possible outcomes, so a
+// word step costs one gather for the draw and the proposed topic's n_kw together.
 #include "common.hpp"
 #include "doc_tile.hpp"
 
@@ -17,9 +19,10 @@ struct SweepArgs {
     int32_t* znew;
     const int32_t* doff;
     const int32_t* chunk_doc;
+    const uint8_t* tokdoc;  // index of each token's document inside its tile
     const int32_t* nkw;
     const int32_t* nk;
-    const uint2* alias;
+    const uint4* alias;     // (split, alias, n_kw[bin], n_kw[alias]) per bin
     const uint32_t* cap;
     int32_t K;
     int32_t mh_steps;
@@ -34,109 +37,250 @@ struct SweepArgs {
     int32_t* long_cnts;
 };
 
-// One token's chain.  `tab` answers n_kd lookups, zdoc[j] is the snapshot topic
-// of the document's j-th token, L the document length.
-template <class Table>
-__device__ __forceinline__ int32_t mh_chain(const SweepArgs& A, const Table& tab,
-                                            const int32_t* zdoc, int32_t L, int32_t w, uint32_t g,
-                                            int32_t z0)
+// The chains of T tokens of one thread, advanced together.
+//
+// A token's chain is a string of dependent memory round trips (alias bin ->
+// proposed topic -> its counts -> accept).  Interleaving T independent chains
+// stage by stage keeps T gathers in flight per lane; every stage below is a
+// fully unrolled loop over the T tokens, so all state lives in registers.
+// tab[u] answers n_kd lookups of token u's document, zdoc[u][j] is the snapshot
+// topic of that document's j-th token, L[u] its length.
+template <int T, class Table>
+__device__ __forceinline__ void mh_chains(const SweepArgs& A, const bool (&valid)[T],
+                                          const Table (&tab)[T], const int32_t* const (&zdoc)[T],
+                                          const int32_t (&L)[T], const int32_t (&w)[T],
+                                          const uint32_t (&g)[T], const int32_t (&z0)[T],
+                                          int32_t (&s)[T])
 {
 #pragma clang fp contract(off)
     const int32_t K = A.K;
-    const int32_t* __restrict__ row = A.nkw + (size_t)w * (size_t)K;
-    const uint2* __restrict__ arow = A.alias + (size_t)w * (size_t)K;
-    const uint32_t capw = A.cap[w];
-    int32_t s = z0;
-    int32_t nds = tab.count(z0);
-    int32_t nws = row[z0];
-    int32_t nks = A.nk[z0];
+    size_t wk[T];
+    uint32_t capw[T];
+    int32_t nds[T], nws[T], nks[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        s[u] = z0[u];
+        wk[u] = 0; capw[u] = 1; nds[u] = 0; nws[u] = 0; nks[u] = 0;
+        if (valid[u]) {
+            wk[u] = (size_t)w[u] * (size_t)K;
+            capw[u] = A.cap[w[u]];
+            nws[u] = A.nkw[wk[u] + (size_t)z0[u]];
+            nks[u] = A.nk[z0[u]];
+            nds[u] = tab[u].count(z0[u]);
+        }
+    }
     for (int32_t j = 0; j < A.mh_steps; ++j) {
-        uint32_t x[4];
-        philox4x32_10(g, 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
         const bool word_step = (A.mode == 0) ? ((j & 1) == 0) : (A.mode == 1);
-        int32_t t;
+        uint32_t x2[T];
+        int32_t t[T], nwt[T];
         if (word_step) {
             // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
-            const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-            const uint32_t rr = mulhi32(x[1], capw);
-            const uint2 e = arow[bin];
-            t = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
+            uint32_t bin[T], rr[T];
+            uint4 e[T];
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                uint32_t x[4];
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                x2[u] = x[2];
+                bin[u] = mulhi32(x[0], (uint32_t)K);
+                rr[u] = mulhi32(x[1], capw[u]);
+                e[u] = make_uint4(0u, 0u, 0u, 0u);
+                if (valid[u]) e[u] = A.alias[wk[u] + bin[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                const bool keep = rr[u] < e[u].x;
+                t[u] = keep ? (int32_t)bin[u] : (int32_t)e[u].y;
+                nwt[u] = keep ? (int32_t)e[u].z : (int32_t)e[u].w;
+            }
         } else {
             // Eq. (9), (12): a random token of the document, or a uniform topic
-            const double u0 = unit_open(x[0]);
-            if (u0 * ((double)L + A.alphabar) < (double)L)
-                t = zdoc[mulhi32(x[1], (uint32_t)L)];
-            else
-                t = (int32_t)mulhi32(x[1], (uint32_t)K);
-        }
-        if (t != s) {
-            const int32_t ndt = tab.count(t);
-            const int32_t nwt = row[t];
-            const int32_t nkt = A.nk[t];
-            const int32_t ms = (s == z0) ? 1 : 0;
-            const int32_t mt = (t == z0) ? 1 : 0;
-            // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
-            double num = (double)(ndt - mt) + A.alpha;
-            num = num * ((double)(nwt - mt) + A.beta);
-            num = num * ((double)(nks - ms) + A.betabar);
-            double den = (double)(nds - ms) + A.alpha;
-            den = den * ((double)(nws - ms) + A.beta);
-            den = den * ((double)(nkt - mt) + A.betabar);
-            if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
-                num = num * ((double)nws + A.beta);
-                num = num * ((double)nkt + A.betabar);
-                den = den * ((double)nwt + A.beta);
-                den = den * ((double)nks + A.betabar);
-            } else {          // Eq. (11): times p_d(s)/p_d(t)
-                num = num * ((double)nds + A.alpha);
-                den = den * ((double)ndt + A.alpha);
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                uint32_t x[4];
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                x2[u] = x[2];
+                t[u] = s[u];
+                nwt[u] = 0;
+                if (valid[u]) {
+                    const double u0 = unit_open(x[0]);
+                    if (u0 * ((double)L[u] + A.alphabar) < (double)L[u])
+                        t[u] = zdoc[u][mulhi32(x[1], (uint32_t)L[u])];
+                    else
+                        t[u] = (int32_t)mulhi32(x[1], (uint32_t)K);
+                }
             }
-            const double u = unit_open(x[2]);
-            if (u * den < num) {
-                s = t;
-                nds = ndt;
-                nws = nwt;
-                nks = nkt;
+        }
+        int32_t ndt[T], nkt[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            ndt[u] = 0; nkt[u] = 0;
+            if (valid[u] && t[u] != s[u]) {
+                if (!word_step) nwt[u] = A.nkw[wk[u] + (size_t)t[u]];
+                nkt[u] = A.nk[t[u]];
+                ndt[u] = tab[u].count(t[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            if (valid[u] && t[u] != s[u]) {
+                const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
+                const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
+                // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
+                double num = (double)(ndt[u] - mt) + A.alpha;
+                num = num * ((double)(nwt[u] - mt) + A.beta);
+                num = num * ((double)(nks[u] - ms) + A.betabar);
+                double den = (double)(nds[u] - ms) + A.alpha;
+                den = den * ((double)(nws[u] - ms) + A.beta);
+                den = den * ((double)(nkt[u] - mt) + A.betabar);
+                if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
+                    num = num * ((double)nws[u] + A.beta);
+                    num = num * ((double)nkt[u] + A.betabar);
+                    den = den * ((double)nwt[u] + A.beta);
+                    den = den * ((double)nks[u] + A.betabar);
+                } else {          // Eq. (11): times p_d(s)/p_d(t)
+                    num = num * ((double)nds[u] + A.alpha);
+                    den = den * ((double)ndt[u] + A.alpha);
+                }
+                const double uu = unit_open(x2[u]);
+                if (uu * den < num) {
+                    s[u] = t[u];
+                    nds[u] = ndt[u];
+                    nws[u] = nwt[u];
+                    nks[u] = nkt[u];
+                }
             }
         }
     }
-    return s;
 }
 
-__global__ __launch_bounds__(1024) void sweep_tiles_kernel(SweepArgs A)
+// T = tokens per thread; a tile has at most T * blockDim.x tokens.  MAXB bounds
+// the block size so that small blocks may use more registers per thread.
+template <int T, int MAXB>
+__global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
 {
     extern __shared__ int32_t smem[];
     const int32_t c = blockIdx.x;
     const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
     if (A.doff[d1] - A.doff[d0] > A.cap_tokens) return;  // a long document: other kernel
-    const DocTile T = load_doc_tile(smem, A.cap_tokens, A.z, A.doff, d0, d1);
-    for (int32_t i = threadIdx.x; i < T.ntok; i += blockDim.x) {
-        const int32_t dl = find_doc(T.sdoff, T.nd, i);
-        const int32_t b = T.sdoff[dl];
-        const int32_t L = T.sdoff[dl + 1] - b;
-        const uint32_t g = (uint32_t)(T.tok0 + i);
-        A.znew[g] = mh_chain(A, T.table(dl), T.zs + b, L, A.word[g], g, T.zs[i]);
+    const DocTile tile = load_doc_tile(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
+    bool valid[T];
+    PackedDocTable tab[T];
+    const int32_t* zdoc[T];
+    int32_t L[T], w[T], z0[T], s[T];
+    uint32_t g[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        const int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+        valid[u] = i < tile.ntok;
+        tab[u] = PackedDocTable{tile.tab, 2u};
+        zdoc[u] = tile.zs;
+        L[u] = 1; w[u] = 0; z0[u] = 0; g[u] = 0;
+        if (valid[u]) {
+            g[u] = (uint32_t)(tile.tok0 + i);
+            const int32_t dl = (int32_t)A.tokdoc[g[u]];
+            const int32_t b = tile.sdoff[dl];
+            L[u] = tile.sdoff[dl + 1] - b;
+            tab[u] = tile.table(dl);
+            zdoc[u] = tile.zs + b;
+            z0[u] = tile.zs[i];
+            w[u] = A.word[g[u]];
+        }
     }
+    mh_chains<T>(A, valid, tab, zdoc, L, w, g, z0, s);
+#pragma unroll
+    for (int u = 0; u < T; ++u)
+        if (valid[u]) A.znew[g[u]] = s[u];
 }
 
 __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
 {
+    constexpr int T = 2;
     const int32_t d = A.long_doc[blockIdx.x];
     const int32_t tok0 = A.doff[d];
-    const int32_t L = A.doff[d + 1] - tok0;
+    const int32_t Ld = A.doff[d + 1] - tok0;
     const int64_t s0 = A.long_slot[blockIdx.x];
-    const DocTable<true> tab = load_long_doc(A.long_keys + s0, A.long_cnts + s0, A.z + tok0, L);
-    for (int32_t i = threadIdx.x; i < L; i += blockDim.x) {
-        const uint32_t g = (uint32_t)(tok0 + i);
-        A.znew[g] = mh_chain(A, tab, A.z + tok0, L, A.word[g], g, A.z[g]);
+    const GlobalDocTable table =
+        load_long_doc(A.long_keys + s0, A.long_cnts + s0, A.z + tok0, Ld);
+    for (int32_t base = 0; base < Ld; base += T * (int32_t)blockDim.x) {
+        bool valid[T];
+        GlobalDocTable tab[T];
+        const int32_t* zdoc[T];
+        int32_t L[T], w[T], z0[T], s[T];
+        uint32_t g[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            const int32_t i = base + (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+            valid[u] = i < Ld;
+            tab[u] = table;
+            zdoc[u] = A.z + tok0;
+            L[u] = Ld;
+            g[u] = (uint32_t)(tok0 + (valid[u] ? i : 0));
+            w[u] = A.word[g[u]];
+            z0[u] = A.z[g[u]];
+        }
+        mh_chains<T>(A, valid, tab, zdoc, L, w, g, z0, s);
+#pragma unroll
+        for (int u = 0; u < T; ++u)
+            if (valid[u]) A.znew[g[u]] = s[u];
     }
+}
+
+template <int T, int MAXB>
+int launch_tiles_tb(lda_ctx* c, const SweepArgs& A, size_t lds)
+{
+    auto kern = sweep_tiles_kernel<T, MAXB>;
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, dim3(c->n_chunks), dim3(c->sweep_block), lds, c->stream, A);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
+
+template <int T>
+int launch_tiles_t(lda_ctx* c, const SweepArgs& A, size_t lds)
+{
+    if (c->sweep_block <= 256) return launch_tiles_tb<T, 256>(c, A, lds);
+    if (c->sweep_block <= 512) return launch_tiles_tb<T, 512>(c, A, lds);
+    return launch_tiles_tb<T, 1024>(c, A, lds);
+}
+
+// tokdoc[g] = index of token g's document inside its tile (0 for long documents)
+__global__ __launch_bounds__(256) void tokdoc_kernel(const int32_t* __restrict__ doff,
+                                                     const int32_t* __restrict__ chunk_doc,
+                                                     int32_t cap_tokens,
+                                                     uint8_t* __restrict__ tokdoc)
+{
+    const int32_t c = blockIdx.x;
+    const int32_t d0 = chunk_doc[c], d1 = chunk_doc[c + 1];
+    const int32_t tok0 = doff[d0], ntok = doff[d1] - tok0;
+    const bool is_long = ntok > cap_tokens;
+    for (int32_t i = threadIdx.x; i < ntok; i += blockDim.x) {
+        int32_t lo = 0, hi = d1 - d0;  // doff[d0+lo] - tok0 <= i < doff[d0+hi] - tok0
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (doff[d0 + mid] - tok0 <= i) lo = mid; else hi = mid;
+        }
+        tokdoc[tok0 + i] = is_long ? (uint8_t)0 : (uint8_t)lo;
+    }
+}
+
+int launch_tokdoc(lda_ctx* c)
+{
+    if (c->n_chunks > 0) {
+        hipLaunchKernelGGL(tokdoc_kernel, dim3(c->n_chunks), dim3(256), 0, c->stream, c->d_doff,
+                           c->d_chunk_doc, c->chunk_tokens, c->d_tokdoc);
+        LDA_HIP(c, hipGetLastError());
+    }
+    return LDA_OK;
 }
 
 int launch_sweep(lda_ctx* c, int32_t mh_steps)
 {
     SweepArgs A{};
     A.word = c->d_word; A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff;
-    A.chunk_doc = c->d_chunk_doc; A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias;
+    A.chunk_doc = c->d_chunk_doc; A.tokdoc = c->d_tokdoc; A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias;
     A.cap = c->d_cap; A.K = c->K; A.mh_steps = mh_steps; A.mode = c->opt.proposal_mode;
     A.cap_tokens = c->chunk_tokens;
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
@@ -145,12 +289,16 @@ int launch_sweep(lda_ctx* c, int32_t mh_steps)
     A.long_keys = c->d_long_keys; A.long_cnts = c->d_long_cnts;
     const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
     if (c->n_chunks > 0) {
-        if (lds > 48 * 1024)
-            LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(sweep_tiles_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(sweep_tiles_kernel, dim3(c->n_chunks), dim3(c->sweep_block), lds,
-                           c->stream, A);
-        LDA_HIP(c, hipGetLastError());
+        const int tpt = (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
+        int rc;
+        if (tpt <= 1) rc = launch_tiles_t<1>(c, A, lds);
+        else if (tpt <= 2) rc = launch_tiles_t<2>(c, A, lds);
+        else if (tpt <= 4) rc = launch_tiles_t<4>(c, A, lds);
+        else if (tpt <= 6) rc = launch_tiles_t<6>(c, A, lds);
+        else if (tpt <= 8) rc = launch_tiles_t<8>(c, A, lds);
+        else return fail(c, LDA_ERR_ARG, "sweep: more than 8 tokens per thread (tile %d, block %d)",
+                         c->chunk_tokens, c->sweep_block);
+        if (rc != LDA_OK) return rc;
     }
     if (c->n_long > 0) {
         hipLaunchKernelGGL(sweep_long_docs_kernel, dim3(c->n_long), dim3(1024), 0, c->stream, A);
@@ -166,8 +314,8 @@ __global__ __launch_bounds__(256) void ndk_row_tile_kernel(const int32_t* z, con
                                                            int32_t K, int32_t* row)
 {
     extern __shared__ int32_t smem[];
-    const DocTile T = load_doc_tile(smem, cap_tokens, z, doff, d, d + 1);
-    const DocTable<false> tab = T.table(0);
+    const DocTile T = load_doc_tile(smem, cap_tokens, z, doff, nullptr, d, d + 1);
+    const PackedDocTable tab = T.table(0);
     for (int32_t k = threadIdx.x; k < K; k += blockDim.x) row[k] = T.ntok > 0 ? tab.count(k) : 0;
 }
 
@@ -177,7 +325,7 @@ __global__ __launch_bounds__(1024) void ndk_row_long_kernel(const int32_t* z, co
 {
     const int32_t tok0 = doff[d];
     const int32_t L = doff[d + 1] - tok0;
-    const DocTable<true> tab = load_long_doc(keys, cnts, z + tok0, L);
+    const GlobalDocTable tab = load_long_doc(keys, cnts, z + tok0, L);
     for (int32_t k = threadIdx.x; k < K; k += blockDim.x) row[k] = tab.count(k);
 }
 
