@@ -22,14 +22,6 @@ namespace {
 
 constexpr int kMaxWaves = 16;
 
-__device__ __forceinline__ uint64_t shfl_up_u64(uint64_t v, int delta)
-{
-    const uint32_t lo = __shfl_up((uint32_t)v, delta, kWave);
-    const uint32_t hi = __shfl_up((uint32_t)(v >> 32), delta, kWave);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-
 __device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
 {
 #pragma unroll

@@ -147,9 +147,10 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
 
     // sweep tiling parameters (LDS: 12 bytes per token + 4 per document).  A packed n_kd
-    // slot holds counts up to 4095 and a one-byte document index, which bound the tile.
+    // slot holds counts up to 4095, a token's slot index takes 12 bits and its document index
+    // one byte, which bound the tile.
     c->chunk_tokens = o.sweep_chunk_tokens > 0 ? o.sweep_chunk_tokens : 512;
-    c->chunk_tokens = std::max(64, std::min((c->chunk_tokens / 64) * 64, 4032));
+    c->chunk_tokens = std::max(64, std::min((c->chunk_tokens / 64) * 64, (int)kMaxTileTokens / 64 * 64));
     c->chunk_docs = std::max(16, std::min(255, c->chunk_tokens / 4));
     c->sweep_block = o.sweep_block_threads > 0 ? o.sweep_block_threads : 256;
     c->sweep_block = std::max(64, std::min(1024, (c->sweep_block / 64) * 64));

@@ -4,8 +4,10 @@
 // is kept in 2L slots (load factor <= 1/2), built from the document's
 // assignments when a workgroup picks the document up.  Documents that fit an LDS
 // tile pack (count << 20 | topic) into one 32-bit slot next to the document's z
-// values; documents too long for a tile keep (topic, count) in two arrays of a
-// global-memory workspace.
+// values, and every token remembers the slot of its own topic, so the counts of
+// a token's own topic and of a topic copied from another token of the document
+// need no probing.  Documents too long for a tile keep (topic, count) in two
+// arrays of a global-memory workspace.
 #pragma once
 
 #include "common.hpp"
@@ -18,47 +20,67 @@ constexpr int kTopicBits = 20;                       // packed slots: topic < 2^
 constexpr uint32_t kTopicMask = (1u << kTopicBits) - 1u;
 constexpr int32_t kMaxPackedTopics = (1 << kTopicBits) - 1;
 constexpr int32_t kMaxPackedCount = (1 << (32 - kTopicBits)) - 1;  // 4095 tokens per document
+constexpr int32_t kMaxTileTokens = 2016;  // a token's slot index (< 2 * tile tokens) takes 12 bits
 
-// Slot of topic k in a table of `slots` < 2^16 entries.  Both multiplies are
-// 24-bit (full rate on the vector ALU): a 16-bit golden-ratio multiplier spreads
-// k, the middle 16 bits of the product are scaled to [0, slots).
-__device__ __forceinline__ uint32_t packed_slot(int32_t k, uint32_t slots)
+// Bucket of topic k in a table of `buckets` < 2^16 two-slot buckets.  Both
+// multiplies are 24-bit (full rate on the vector ALU): a 16-bit golden-ratio
+// multiplier spreads k, the middle 16 bits of the product are scaled to [0, buckets).
+__device__ __forceinline__ uint32_t packed_bucket(int32_t k, uint32_t buckets)
 {
     const uint32_t h = (__umul24((uint32_t)k, 40503u) >> 4) & 0xFFFFu;
-    return __umul24(h, slots) >> 16;
+    return __umul24(h, buckets) >> 16;
 }
 
-// LDS table of one document.
+// LDS table of one document: L buckets of two packed slots (load factor <= 1/2),
+// probed one whole bucket (one 8-byte LDS read) at a time.
 struct PackedDocTable {
-    uint32_t* tab;
-    uint32_t slots;  // 2 * L, 2 <= slots <= 8190
+    uint32_t* tab;     // 8-byte aligned
+    uint32_t buckets;  // = L, 1 <= buckets <= 2047
 
-    __device__ __forceinline__ void insert(int32_t k) const
+    // Adds one token of topic k; returns the slot (relative to tab) that holds k.
+    __device__ __forceinline__ uint32_t insert(int32_t k) const
     {
-        uint32_t s = packed_slot(k, slots);
-        for (uint32_t n = 0; n < slots; ++n) {
-            const uint32_t prev = atomicCAS(&tab[s], kEmptySlot, (1u << kTopicBits) | (uint32_t)k);
-            if (prev == kEmptySlot) return;
-            if ((prev & kTopicMask) == (uint32_t)k) {
-                atomicAdd(&tab[s], 1u << kTopicBits);
-                return;
+        uint32_t b = packed_bucket(k, buckets);
+        const uint32_t fresh = (1u << kTopicBits) | (uint32_t)k;
+        for (uint32_t n = 0; n < buckets; ++n) {
+#pragma unroll
+            for (uint32_t j = 0; j < 2; ++j) {
+                const uint32_t s = 2 * b + j;
+                const uint32_t prev = atomicCAS(&tab[s], kEmptySlot, fresh);
+                if (prev == kEmptySlot) return s;
+                if ((prev & kTopicMask) == (uint32_t)k) {
+                    atomicAdd(&tab[s], 1u << kTopicBits);
+                    return s;
+                }
             }
-            s = (s + 1 == slots) ? 0u : s + 1;
+            b = (b + 1 == buckets) ? 0u : b + 1;
         }
+        return 0;  // not reached: at most L distinct topics in 2L slots
     }
 
-    // n_kd of topic k (0 when the document has no token of it).  An empty slot
-    // always exists because the load factor is <= 1/2.
+    // n_kd of topic k (0 when the document has no token of it).  Slots of a bucket
+    // fill in order, so an empty slot ends the search.
     __device__ __forceinline__ int32_t count(int32_t k) const
     {
-        uint32_t s = packed_slot(k, slots);
-        for (uint32_t n = 0; n < slots; ++n) {
-            const uint32_t v = tab[s];
-            if ((v & kTopicMask) == (uint32_t)k) return (int32_t)(v >> kTopicBits);
-            if (v == kEmptySlot) return 0;
-            s = (s + 1 == slots) ? 0u : s + 1;
+        uint32_t b = packed_bucket(k, buckets);
+        int32_t result = 0;
+        for (uint32_t n = 0; n < buckets; ++n) {
+            const uint2 v = reinterpret_cast<const uint2*>(tab)[b];
+            // an empty slot never matches: its topic field is 2^20 - 1 > any topic
+            const bool hit0 = (v.x & kTopicMask) == (uint32_t)k;
+            const bool hit1 = (v.y & kTopicMask) == (uint32_t)k;
+            if (hit0) result = (int32_t)(v.x >> kTopicBits);
+            if (hit1) result = (int32_t)(v.y >> kTopicBits);
+            if (hit0 || hit1 || v.x == kEmptySlot || v.y == kEmptySlot) break;
+            b = (b + 1 == buckets) ? 0u : b + 1;
         }
-        return 0;
+        return result;
+    }
+
+    // count of the topic stored in a known slot (as returned by insert)
+    __device__ __forceinline__ int32_t count_at(uint32_t slot) const
+    {
+        return (int32_t)(tab[slot] >> kTopicBits);
     }
 };
 

@@ -9,7 +9,8 @@
 namespace lda {
 
 struct DocTile {
-    int32_t* zs;     // [cap_tokens]   snapshot topics of the tile's tokens
+    uint32_t* zs;    // [cap_tokens]   per token: snapshot topic | slot of that topic << 20
+                     //                (slot relative to the document's table)
     uint32_t* tab;   // [2*cap_tokens] packed slots, document d owns [2*sdoff[d], 2*sdoff[d+1])
     int32_t* sdoff;  // [cap_docs+1]   token offsets relative to the tile start
     int32_t nd;      // documents in the tile
@@ -19,7 +20,7 @@ struct DocTile {
     __device__ __forceinline__ PackedDocTable table(int32_t dl) const
     {
         const int32_t b = sdoff[dl];
-        return PackedDocTable{tab + 2 * b, (uint32_t)(2 * (sdoff[dl + 1] - b))};
+        return PackedDocTable{tab + 2 * b, (uint32_t)(sdoff[dl + 1] - b)};
     }
 };
 
@@ -38,7 +39,7 @@ __device__ __forceinline__ DocTile load_doc_tile(int32_t* smem, int32_t cap_toke
                                                  int32_t d1)
 {
     DocTile t;
-    t.zs = smem;
+    t.zs = reinterpret_cast<uint32_t*>(smem);
     t.tab = reinterpret_cast<uint32_t*>(smem + cap_tokens);
     t.sdoff = smem + 3 * (size_t)cap_tokens;
     t.nd = d1 - d0;
@@ -47,13 +48,14 @@ __device__ __forceinline__ DocTile load_doc_tile(int32_t* smem, int32_t cap_toke
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int32_t i = tid; i <= t.nd; i += nt) t.sdoff[i] = doff[d0 + i] - t.tok0;
     for (int32_t i = tid; i < t.ntok; i += nt) {
-        t.zs[i] = z[t.tok0 + i];
+        t.zs[i] = (uint32_t)z[t.tok0 + i];
         reinterpret_cast<uint2*>(t.tab)[i] = make_uint2(kEmptySlot, kEmptySlot);
     }
     __syncthreads();
     for (int32_t i = tid; i < t.ntok; i += nt) {
         const int32_t dl = tokdoc ? (int32_t)tokdoc[t.tok0 + i] : find_doc(t.sdoff, t.nd, i);
-        t.table(dl).insert(t.zs[i]);
+        const uint32_t zi = t.zs[i];
+        t.zs[i] = zi | (t.table(dl).insert((int32_t)zi) << kTopicBits);  // own element only
     }
     __syncthreads();
     return t;

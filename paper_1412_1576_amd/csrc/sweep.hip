@@ -37,44 +37,66 @@ struct SweepArgs {
     int32_t* long_cnts;
 };
 
+// A token's document as the chain sees it: n_kd of an arbitrary topic, and the
+// topic and n_kd of the document's j-th token.
+struct TileDocView {  // document staged in an LDS tile
+    PackedDocTable tab;
+    const uint32_t* zs;  // the document's packed (topic | slot << 20) entries
+    int32_t L;
+    __device__ __forceinline__ int32_t count(int32_t k) const { return tab.count(k); }
+    __device__ __forceinline__ void token(uint32_t j, int32_t& topic, int32_t& nd) const
+    {
+        const uint32_t v = zs[j];
+        topic = (int32_t)(v & kTopicMask);
+        nd = tab.count_at(v >> kTopicBits);
+    }
+};
+
+struct LongDocView {  // document hashed in the global workspace
+    GlobalDocTable tab;
+    const int32_t* z;
+    int32_t L;
+    __device__ __forceinline__ int32_t count(int32_t k) const { return tab.count(k); }
+    __device__ __forceinline__ void token(uint32_t j, int32_t& topic, int32_t& nd) const
+    {
+        topic = z[j];
+        nd = tab.count(topic);
+    }
+};
+
 // The chains of T tokens of one thread, advanced together.
 //
-// A token's chain is a string of dependent memory round trips (alias bin ->
-// proposed topic -> its counts -> accept).  Interleaving T independent chains
-// stage by stage keeps T gathers in flight per lane; every stage below is a
-// fully unrolled loop over the T tokens, so all state lives in registers.
-// tab[u] answers n_kd lookups of token u's document, zdoc[u][j] is the snapshot
-// topic of that document's j-th token, L[u] its length.
-template <int T, class Table>
-__device__ __forceinline__ void mh_chains(const SweepArgs& A, const bool (&valid)[T],
-                                          const Table (&tab)[T], const int32_t* const (&zdoc)[T],
-                                          const int32_t (&L)[T], const int32_t (&w)[T],
-                                          const uint32_t (&g)[T], const int32_t (&z0)[T],
-                                          int32_t (&s)[T])
+// Interleaving T independent chains stage by stage keeps T gathers in flight per
+// lane; every stage below is a fully unrolled loop over the T tokens, so all state
+// lives in registers.  doc[u] is token u's document, own[u] its position in it,
+// w[u] its word, g[u] its CSR position (the Philox counter).  The accept test is
+// evaluated without branching; a step with t == s leaves the state unchanged.
+template <int T, class DocView>
+__device__ __forceinline__ void mh_chains(const SweepArgs& A, const DocView (&doc)[T],
+                                          const uint32_t (&own)[T], const int32_t (&w)[T],
+                                          const uint32_t (&g)[T], int32_t (&s)[T])
 {
 #pragma clang fp contract(off)
     const int32_t K = A.K;
     size_t wk[T];
     uint32_t capw[T];
-    int32_t nds[T], nws[T], nks[T];
+    int32_t z0[T], nds[T], nws[T], nks[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
+        doc[u].token(own[u], z0[u], nds[u]);
         s[u] = z0[u];
-        wk[u] = 0; capw[u] = 1; nds[u] = 0; nws[u] = 0; nks[u] = 0;
-        if (valid[u]) {
-            wk[u] = (size_t)w[u] * (size_t)K;
-            capw[u] = A.cap[w[u]];
-            nws[u] = A.nkw[wk[u] + (size_t)z0[u]];
-            nks[u] = A.nk[z0[u]];
-            nds[u] = tab[u].count(z0[u]);
-        }
+        wk[u] = (size_t)w[u] * (size_t)K;
+        capw[u] = A.cap[w[u]];
+        nws[u] = A.nkw[wk[u] + (size_t)z0[u]];
+        nks[u] = A.nk[z0[u]];
     }
     for (int32_t j = 0; j < A.mh_steps; ++j) {
         const bool word_step = (A.mode == 0) ? ((j & 1) == 0) : (A.mode == 1);
         uint32_t x2[T];
-        int32_t t[T], nwt[T];
+        int32_t t[T], ndt[T], nwt[T], nkt[T];
         if (word_step) {
-            // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
+            // Fig. 2: uniform bin, uniform height, keep the bin or take its alias;
+            // the bin brings n_kw of both outcomes along
             uint32_t bin[T], rr[T];
             uint4 e[T];
 #pragma unroll
@@ -84,15 +106,17 @@ __device__ __forceinline__ void mh_chains(const SweepArgs& A, const bool (&valid
                 x2[u] = x[2];
                 bin[u] = mulhi32(x[0], (uint32_t)K);
                 rr[u] = mulhi32(x[1], capw[u]);
-                e[u] = make_uint4(0u, 0u, 0u, 0u);
-                if (valid[u]) e[u] = A.alias[wk[u] + bin[u]];
+                e[u] = A.alias[wk[u] + bin[u]];
             }
 #pragma unroll
             for (int u = 0; u < T; ++u) {
                 const bool keep = rr[u] < e[u].x;
                 t[u] = keep ? (int32_t)bin[u] : (int32_t)e[u].y;
                 nwt[u] = keep ? (int32_t)e[u].z : (int32_t)e[u].w;
+                nkt[u] = A.nk[t[u]];
             }
+#pragma unroll
+            for (int u = 0; u < T; ++u) ndt[u] = doc[u].count(t[u]);
         } else {
             // Eq. (9), (12): a random token of the document, or a uniform topic
 #pragma unroll
@@ -100,56 +124,45 @@ __device__ __forceinline__ void mh_chains(const SweepArgs& A, const bool (&valid
                 uint32_t x[4];
                 philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
                 x2[u] = x[2];
-                t[u] = s[u];
-                nwt[u] = 0;
-                if (valid[u]) {
-                    const double u0 = unit_open(x[0]);
-                    if (u0 * ((double)L[u] + A.alphabar) < (double)L[u])
-                        t[u] = zdoc[u][mulhi32(x[1], (uint32_t)L[u])];
-                    else
-                        t[u] = (int32_t)mulhi32(x[1], (uint32_t)K);
+                const double u0 = unit_open(x[0]);
+                const double Ld = (double)doc[u].L;
+                if (u0 * (Ld + A.alphabar) < Ld) {
+                    doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[u], ndt[u]);
+                } else {
+                    t[u] = (int32_t)mulhi32(x[1], (uint32_t)K);
+                    ndt[u] = doc[u].count(t[u]);
                 }
-            }
-        }
-        int32_t ndt[T], nkt[T];
-#pragma unroll
-        for (int u = 0; u < T; ++u) {
-            ndt[u] = 0; nkt[u] = 0;
-            if (valid[u] && t[u] != s[u]) {
-                if (!word_step) nwt[u] = A.nkw[wk[u] + (size_t)t[u]];
                 nkt[u] = A.nk[t[u]];
-                ndt[u] = tab[u].count(t[u]);
+                nwt[u] = nws[u];
+                if (t[u] != s[u]) nwt[u] = A.nkw[wk[u] + (size_t)t[u]];
             }
         }
 #pragma unroll
         for (int u = 0; u < T; ++u) {
-            if (valid[u] && t[u] != s[u]) {
-                const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
-                const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
-                // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
-                double num = (double)(ndt[u] - mt) + A.alpha;
-                num = num * ((double)(nwt[u] - mt) + A.beta);
-                num = num * ((double)(nks[u] - ms) + A.betabar);
-                double den = (double)(nds[u] - ms) + A.alpha;
-                den = den * ((double)(nws[u] - ms) + A.beta);
-                den = den * ((double)(nkt[u] - mt) + A.betabar);
-                if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
-                    num = num * ((double)nws[u] + A.beta);
-                    num = num * ((double)nkt[u] + A.betabar);
-                    den = den * ((double)nwt[u] + A.beta);
-                    den = den * ((double)nks[u] + A.betabar);
-                } else {          // Eq. (11): times p_d(s)/p_d(t)
-                    num = num * ((double)nds[u] + A.alpha);
-                    den = den * ((double)ndt[u] + A.alpha);
-                }
-                const double uu = unit_open(x2[u]);
-                if (uu * den < num) {
-                    s[u] = t[u];
-                    nds[u] = ndt[u];
-                    nws[u] = nwt[u];
-                    nks[u] = nkt[u];
-                }
+            const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
+            const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
+            // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
+            double num = (double)(ndt[u] - mt) + A.alpha;
+            num = num * ((double)(nwt[u] - mt) + A.beta);
+            num = num * ((double)(nks[u] - ms) + A.betabar);
+            double den = (double)(nds[u] - ms) + A.alpha;
+            den = den * ((double)(nws[u] - ms) + A.beta);
+            den = den * ((double)(nkt[u] - mt) + A.betabar);
+            if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
+                num = num * ((double)nws[u] + A.beta);
+                num = num * ((double)nkt[u] + A.betabar);
+                den = den * ((double)nwt[u] + A.beta);
+                den = den * ((double)nks[u] + A.betabar);
+            } else {          // Eq. (11): times p_d(s)/p_d(t)
+                num = num * ((double)nds[u] + A.alpha);
+                den = den * ((double)ndt[u] + A.alpha);
             }
+            const double uu = unit_open(x2[u]);
+            const bool accept = (t[u] != s[u]) && (uu * den < num);
+            s[u] = accept ? t[u] : s[u];
+            nds[u] = accept ? ndt[u] : nds[u];
+            nws[u] = accept ? nwt[u] : nws[u];
+            nks[u] = accept ? nkt[u] : nks[u];
         }
     }
 }
@@ -162,35 +175,33 @@ __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
     extern __shared__ int32_t smem[];
     const int32_t c = blockIdx.x;
     const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
-    if (A.doff[d1] - A.doff[d0] > A.cap_tokens) return;  // a long document: other kernel
+    const int32_t ntok = A.doff[d1] - A.doff[d0];
+    if (ntok > A.cap_tokens || ntok == 0) return;  // a long document (other kernel) / nothing
     const DocTile tile = load_doc_tile(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
-    bool valid[T];
-    PackedDocTable tab[T];
-    const int32_t* zdoc[T];
-    int32_t L[T], w[T], z0[T], s[T];
-    uint32_t g[T];
+    TileDocView doc[T];
+    uint32_t own[T], g[T];
+    int32_t w[T], s[T];
+    bool live[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
-        const int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
-        valid[u] = i < tile.ntok;
-        tab[u] = PackedDocTable{tile.tab, 2u};
-        zdoc[u] = tile.zs;
-        L[u] = 1; w[u] = 0; z0[u] = 0; g[u] = 0;
-        if (valid[u]) {
-            g[u] = (uint32_t)(tile.tok0 + i);
-            const int32_t dl = (int32_t)A.tokdoc[g[u]];
-            const int32_t b = tile.sdoff[dl];
-            L[u] = tile.sdoff[dl + 1] - b;
-            tab[u] = tile.table(dl);
-            zdoc[u] = tile.zs + b;
-            z0[u] = tile.zs[i];
-            w[u] = A.word[g[u]];
-        }
+        // lanes past the end of the tile redo its last token and drop the result:
+        // no lane is ever masked off inside the chains
+        int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+        live[u] = i < tile.ntok;
+        if (!live[u]) i = tile.ntok - 1;
+        g[u] = (uint32_t)(tile.tok0 + i);
+        const int32_t dl = (int32_t)A.tokdoc[g[u]];
+        const int32_t b = tile.sdoff[dl];
+        doc[u].L = tile.sdoff[dl + 1] - b;
+        doc[u].tab = tile.table(dl);
+        doc[u].zs = tile.zs + b;
+        own[u] = (uint32_t)(i - b);
+        w[u] = A.word[g[u]];
     }
-    mh_chains<T>(A, valid, tab, zdoc, L, w, g, z0, s);
+    mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
     for (int u = 0; u < T; ++u)
-        if (valid[u]) A.znew[g[u]] = s[u];
+        if (live[u]) A.znew[g[u]] = s[u];
 }
 
 __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
@@ -203,26 +214,26 @@ __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
     const GlobalDocTable table =
         load_long_doc(A.long_keys + s0, A.long_cnts + s0, A.z + tok0, Ld);
     for (int32_t base = 0; base < Ld; base += T * (int32_t)blockDim.x) {
-        bool valid[T];
-        GlobalDocTable tab[T];
-        const int32_t* zdoc[T];
-        int32_t L[T], w[T], z0[T], s[T];
-        uint32_t g[T];
+        LongDocView doc[T];
+        uint32_t own[T], g[T];
+        int32_t w[T], s[T];
+        bool live[T];
 #pragma unroll
         for (int u = 0; u < T; ++u) {
-            const int32_t i = base + (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
-            valid[u] = i < Ld;
-            tab[u] = table;
-            zdoc[u] = A.z + tok0;
-            L[u] = Ld;
-            g[u] = (uint32_t)(tok0 + (valid[u] ? i : 0));
+            int32_t i = base + (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+            live[u] = i < Ld;
+            if (!live[u]) i = Ld - 1;
+            doc[u].tab = table;
+            doc[u].z = A.z + tok0;
+            doc[u].L = Ld;
+            own[u] = (uint32_t)i;
+            g[u] = (uint32_t)(tok0 + i);
             w[u] = A.word[g[u]];
-            z0[u] = A.z[g[u]];
         }
-        mh_chains<T>(A, valid, tab, zdoc, L, w, g, z0, s);
+        mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
         for (int u = 0; u < T; ++u)
-            if (valid[u]) A.znew[g[u]] = s[u];
+            if (live[u]) A.znew[g[u]] = s[u];
     }
 }
 

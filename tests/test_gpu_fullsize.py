@@ -1,0 +1,93 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot sweep 10^8..10^9 tokens in test time, so after an exhaustive
+comparison of the initial state (z, n_k) it is asked for the chains of sampled
+tokens only, for n_kw rows and alias tables of sampled words (the most frequent
+word -- many rebuild tiles -- and rare ones), and the GPU's post-sweep counts are
+checked against a numpy recount of the GPU's own assignment (a property that
+holds at any size).
+"""
+import numpy as np
+import pytest
+
+from paper_1412_1576_amd import corpus
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lda_mod():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_1412_1576_amd import lda
+    lda.load_library()
+    return lda
+
+
+def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12, seed=123):
+    rng = np.random.default_rng(seed)
+    doff, words = corpus.make_corpus(cfg)
+    N = int(doff[-1])
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed)
+    o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                          lazy_alias=True)
+    # initial state: exhaustive
+    z_init = g.get_z()
+    assert np.array_equal(z_init, o.get_z())
+    assert np.array_equal(g.get_nk(), o.get_nk())
+    freq = np.bincount(words, minlength=cfg.V)
+    order = np.argsort(-freq, kind="stable")
+    sample_words = list(order[:3]) + list(order[[len(order) // 2, -1]]) + \
+        list(rng.choice(cfg.V, n_words - 5, replace=False))
+    for w in sample_words:
+        assert np.array_equal(g.get_nkw_row(w), o.get_nkw_row(w)), "n_kw row %d" % w
+    docs = rng.choice(cfg.D, 20, replace=False)
+    for d in docs:
+        assert np.array_equal(g.get_ndk_row(d), o.get_ndk_row(d)), "n_dk row %d" % d
+    # alias tables of the sampled words
+    g.build_alias()
+    o.build_alias()
+    for w in sample_words:
+        sg, ag, cg = g.get_alias_row(w)
+        so, ao, co = o.get_alias_row(w)
+        assert cg == co and np.array_equal(sg, so) and np.array_equal(ag, ao), "alias row %d" % w
+    # the sweep: sampled chains (tokens of the hottest word, of rare words, uniform ones)
+    ids = np.unique(np.concatenate([
+        rng.choice(N, n_tokens, replace=False),
+        np.flatnonzero(words[: 5_000_000] == order[0])[:200],
+        np.flatnonzero(words[: 5_000_000] == order[-1])[:50],
+        np.array([0, N - 1]),
+    ])).astype(np.int64)
+    want = o.sweep_tokens(0, mh_steps, ids)
+    g.sweep(mh_steps)
+    z_new = g.get_z()
+    assert np.array_equal(z_new[ids], want), \
+        "%d of %d sampled tokens differ" % (int((z_new[ids] != want).sum()), len(ids))
+    assert 0 <= z_new.min() and z_new.max() < cfg.K
+    assert (z_new != z_init).mean() > 0.05  # the sweep did move tokens
+    # rebuilt counts against a recount of the GPU's own assignment
+    g.rebuild_counts()
+    nk = g.get_nk()
+    assert np.array_equal(nk, np.bincount(z_new, minlength=cfg.K))
+    assert int(nk.sum()) == N
+    for w in sample_words[:6]:
+        row = np.bincount(z_new[words == w], minlength=cfg.K)
+        assert np.array_equal(g.get_nkw_row(w), row), "rebuilt n_kw row %d" % w
+    for d in docs[:8]:
+        row = np.bincount(z_new[doff[d]:doff[d + 1]], minlength=cfg.K)
+        assert np.array_equal(g.get_ndk_row(d), row), "rebuilt n_dk row %d" % d
+    g.close()
+    o.close()
+
+
+@pytest.mark.timeout(600)
+def test_c2_full_size_sampled(lda_mod, oracle_mod):
+    cfg = corpus.CONFIGS["c2"]
+    sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps)
+
+
+@pytest.mark.timeout(900)
+def test_c3_full_size_sampled(lda_mod, oracle_mod):
+    """The benchmark's workload (K = 10,000), with the config's own 4 MH steps."""
+    cfg = corpus.CONFIGS["c3"]
+    sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10)
