@@ -43,9 +43,12 @@ def design_bytes_per_token(mh_steps: int) -> float:
     return 12.0 + 8.0 + 16.0 * word_steps + 8.0 * doc_steps
 
 
-# HBM bytes per sweep launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); keyed by (workload, mh_steps).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM-side bytes per sweep launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (profiles/all_kernels_c3_mh2.txt: counter KiB x calibration factor x 1024, fetched +
+# written); keyed by (workload, mh_steps).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {
+    ("c3", 2): (112_957_986.2 * 2.000 + 3_040_537.5 * 1.000) * 1024.0,
+}
 
 
 def cpu_baseline(cfg, doff, words, mh_steps, sample_docs):
