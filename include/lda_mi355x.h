@@ -57,11 +57,13 @@ typedef struct lda_ctx lda_ctx; /* opaque; owns all device memory of one corpus 
 /* Options for lda_init.  A zeroed struct (or a NULL pointer) selects the defaults. */
 typedef struct lda_options {
     void* hip_stream;              /* hipStream_t all work is enqueued on; NULL: the null stream */
-    int32_t dense_rows;            /* number of most frequent word ids [0, dense_rows) whose n_kw row
-                                      is stored dense (hybrid store, Sec. 5); 0: every row dense */
+    int32_t dense_rows;            /* hybrid store (Sec. 5): word ids [0, dense_rows) keep a dense n_kw
+                                      row, the others a sorted (topic, count) list plus a hash row;
+                                      0: every row dense; -1: no dense row */
     int32_t dense_alias_min_count; /* words with corpus frequency >= this draw from a dense K-bin
                                       table, the others from the sparsified mixture (Sec. 4.2);
-                                      0: every word uses the dense table */
+                                      0: every word uses the dense table.  A word that draws from a
+                                      dense table must have a dense row (LDA_ERR_ARG otherwise). */
     int32_t proposal_mode;         /* 0: cycle word,doc,word,... (Eq. 13); 1: word only; 2: doc only */
     int32_t sweep_chunk_tokens;    /* tuning: tokens per sweep workgroup tile; 0: default */
     int32_t sweep_block_threads;   /* tuning: threads per sweep workgroup; 0: default */
@@ -132,6 +134,18 @@ int lda_get_nkw_row(lda_ctx* ctx, int32_t w, int32_t* row);
 int lda_get_ndk_row(lda_ctx* ctx, int64_t d, int32_t* row);
 /* Dense-form table of word w: split [K], alias [K], *cap = bin capacity; needs ALIAS_VALID. */
 int lda_get_alias_row(lda_ctx* ctx, int32_t w, uint32_t* split, uint32_t* alias, uint32_t* cap);
+
+/* Mixture-form tables (Sec. 4.2, the sparsified word-proposal); need ALIAS_VALID.
+ * lda_get_sparse_table: the table of word w over its non-zero topics.  *n = number of entries;
+ * when *n <= cap_entries the entries are written: topics[i] ascending, split[i], and
+ * alias_topic[i] = the topic bin i falls through to.  *cap = bin capacity, *mass = integer mass
+ * QS_w of the sparse term.  LDA_ERR_ARG if the word draws from a dense table.
+ * lda_get_beta_table: the table over beta/(n_k + V beta) shared by all words, split [K],
+ * alias [K] (topic indices), its capacity and integer mass QB. */
+int lda_get_sparse_table(lda_ctx* ctx, int32_t w, int32_t cap_entries, int32_t* n, int32_t* topics,
+                         uint32_t* split, int32_t* alias_topic, uint32_t* cap, uint64_t* mass);
+int lda_get_beta_table(lda_ctx* ctx, uint32_t* split, uint32_t* alias, uint32_t* cap,
+                       uint64_t* mass);
 
 /* Wait for all work enqueued by this context. */
 int lda_sync(lda_ctx* ctx);

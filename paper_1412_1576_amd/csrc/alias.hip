@@ -1,329 +1,370 @@
-// Word-proposal alias tables (LightLDA Sec. 4.2, Eq. 6, Fig. 2), one workgroup
-// per word.
+// Word-proposal tables (LightLDA Sec. 4.2, Eq. 6, Fig. 2).
 //
-// The table is defined on integers so that this parallel build is exact:
-//   a_k  = (n_kw + beta) / (n_k + betabar)                  (fp64, one division)
-//   q0_k = floor(a_k * 2^40),  Q0 = sum q0_k
-//   sh   = smallest shift with (Q0 >> sh) < K * 2^31
-//   q_k  = max(1, q0_k >> sh), Q = sum q_k, C = ceil(Q / K), pad = K*C - Q
-//   m_k  = q_k + (k < pad)                                   (sum m_k = K*C)
-// Bins with m_k < C ("lights", ascending k, exclusive deficit sums Delta_a) are
-// topped up by bins with m_k >= C ("heavies", ascending k, inclusive excess sums
-// X_b).  Pairing the two ascending lists greedily has the closed form
-//   light a : split = m,  alias = heavy b with b = min{b : X_b > Delta_a}
-//   heavy b : a = min{a : Delta_a >= X_b}, split = C + X_b - Delta_a,
-//             alias = next heavy if split < C, else itself
-// so the build is prefix sums over the two lists and one binary search per bin.
-#include "common.hpp"
+// Dense form: one table per word over all K topics, weights (n_kw + beta)/(n_k + betabar).
+// Mixture form (the paper's sparsified table): per word a table over its non-zero
+// topics only, weights n_kw/(n_k + betabar), plus one table shared by all words over
+// beta/(n_k + betabar); the sweep picks the term by the two integer masses QS_w and QB.
+// Every table is built by one workgroup with the generic builder of alias_build.hpp;
+// tables too large for LDS use a global workspace.
+#include "alias_build.hpp"
 
 namespace lda {
 
 namespace {
 
-constexpr int kMaxWaves = 16;
-
-__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v)
+__device__ __forceinline__ uint64_t quantise40(double a)
 {
-#pragma unroll
-    for (int d = kWave / 2; d >= 1; d >>= 1) {
-        const uint32_t lo = __shfl_xor((uint32_t)v, d, kWave);
-        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), d, kWave);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
-// Inclusive prefix sum over the 64 lanes with DPP row shifts and row broadcasts
-// (no LDS traffic): shifts by 1, 2, 3 of the input, then 4 and 8 inside each row of
-// 16 lanes, then the last lane of row 0 / 2 into row 1 / 3 and lane 31 into rows 2, 3.
-__device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t v)
-{
-    const int x = (int)v;
-    int r = x;
-    r += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);  // row_shr:1
-    r += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);  // row_shr:2
-    r += __builtin_amdgcn_update_dpp(0, x, 0x113, 0xf, 0xf, false);  // row_shr:3
-    r += __builtin_amdgcn_update_dpp(0, r, 0x114, 0xf, 0xe, false);  // row_shr:4, lanes 4..15
-    r += __builtin_amdgcn_update_dpp(0, r, 0x118, 0xf, 0xc, false);  // row_shr:8, lanes 8..15
-    r += __builtin_amdgcn_update_dpp(0, r, 0x142, 0xa, 0xf, false);  // row_bcast:15 -> rows 1, 3
-    r += __builtin_amdgcn_update_dpp(0, r, 0x143, 0xc, 0xf, false);  // row_bcast:31 -> rows 2, 3
-    return (uint32_t)r;
-}
-
-// 64-bit inclusive prefix sum of values < 2^46: the low 26 bits and the rest are
-// summed separately (64 terms cannot overflow 32 bits) and recombined.
-__device__ __forceinline__ uint64_t wave_inclusive_scan_u64(uint64_t v)
-{
-    const uint32_t lo = wave_inclusive_scan_u32((uint32_t)v & 0x3FFFFFFu);
-    const uint32_t hi = wave_inclusive_scan_u32((uint32_t)(v >> 26));
-    return ((uint64_t)hi << 26) + (uint64_t)lo;
-}
-
-__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int lane)
-{
-    const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, lane);
-    const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-// First index in [lo, hi] at which the monotone predicate holds; pred(hi) is known
-// to hold.  lo, hi are wave-uniform and all 64 lanes take part: a window of 64
-// consecutive indices first (partners of neighbouring bins are close), then 64-ary
-// narrowing of what is left.
-template <class Pred>
-__device__ __forceinline__ uint32_t wave_first_true(uint32_t lo, uint32_t hi, int lane, Pred pred)
-{
-    {
-        const uint32_t top = (hi - lo > 63u) ? lo + 63u : hi;
-        uint32_t idx = lo + (uint32_t)lane;
-        if (idx > top) idx = top;
-        const uint64_t mask = __ballot(pred(idx));
-        if (mask != 0) return lo + (uint32_t)(__ffsll((unsigned long long)mask) - 1);
-        lo = top + 1;  // top < hi here, because pred(hi) holds
-    }
-    for (;;) {
-        const uint32_t step = (hi - lo) / 63u + 1u;
-        uint32_t idx = lo + (uint32_t)lane * step;
-        if (idx > hi) idx = hi;
-        const uint64_t mask = __ballot(pred(idx));  // lane 63 sits on hi: never empty
-        const uint32_t f = (uint32_t)(__ffsll((unsigned long long)mask) - 1);
-        const uint32_t cand = lo + f * step;
-        if (step == 1u) return cand < hi ? cand : hi;
-        hi = cand < hi ? cand : hi;
-        if (f > 0) lo = lo + (f - 1u) * step + 1u;
-    }
-}
-
-// number of set bits of `mask` below this lane
-__device__ __forceinline__ uint32_t rank_below(uint64_t mask)
-{
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
-
-// floor(a_k * 2^40) for bin k of the word: the only floating-point step
-__device__ __forceinline__ uint64_t bin_q0(const int32_t* __restrict__ row,
-                                           const int32_t* __restrict__ nk, int32_t k, double beta,
-                                           double betabar)
-{
-#pragma clang fp contract(off)
-    const double a = ((double)row[k] + beta) / ((double)nk[k] + betabar);
     return (uint64_t)floor(a * 1099511627776.0);
 }
 
-// One workgroup per word.  Wave v owns the contiguous bins [v*S, (v+1)*S), visited
-// 64 at a time, so global loads and stores are coalesced and bins are met in
-// ascending order.  The quantised weights are kept in LDS as 32-bit values when
-// the table leaves room (recomputed by division when they do not fit).
-__global__ __launch_bounds__(1024) void alias_dense_kernel(const int32_t* __restrict__ nkw,
-                                                           const int32_t* __restrict__ nk,
-                                                           int32_t K, double beta, double betabar,
-                                                           uint4* __restrict__ alias,
-                                                           uint32_t* __restrict__ cap,
-                                                           int32_t use_cache)
+// dense form: entry k is topic k
+struct DenseSrc {
+    const int32_t* __restrict__ row;
+    const int32_t* __restrict__ nk;
+    double beta, betabar;
+    __device__ __forceinline__ uint64_t q0(int32_t k) const
+    {
+#pragma clang fp contract(off)
+        return quantise40(((double)row[k] + beta) / ((double)nk[k] + betabar));
+    }
+};
+
+// A dense bin also carries the word-topic counts of its two outcomes, so the sweep's
+// accept test needs no second gather.
+struct DenseSink {
+    uint4* __restrict__ out;
+    const int32_t* __restrict__ row;
+    __device__ __forceinline__ void put(int32_t k, uint32_t split, uint32_t al) const
+    {
+        out[k] = make_uint4(split, al, (uint32_t)row[k], (uint32_t)row[al]);
+    }
+};
+
+// sparse term of the mixture: entry i is the word's i-th non-zero topic (ascending)
+struct SparseSrc {
+    const int32_t* __restrict__ topic;
+    const int32_t* __restrict__ count;
+    const int32_t* __restrict__ nk;
+    double betabar;
+    __device__ __forceinline__ uint64_t q0(int32_t i) const
+    {
+#pragma clang fp contract(off)
+        return quantise40((double)count[i] / ((double)nk[topic[i]] + betabar));
+    }
+};
+
+// mixture bin: (split, own topic, alias topic, n_kw[own]) and (n_kw[alias], -, -, -)
+struct SparseSink {
+    uint4* __restrict__ out;
+    const int32_t* __restrict__ topic;
+    const int32_t* __restrict__ count;
+    __device__ __forceinline__ void put(int32_t i, uint32_t split, uint32_t al) const
+    {
+        out[2 * (size_t)i] =
+            make_uint4(split, (uint32_t)topic[i], (uint32_t)topic[al], (uint32_t)count[i]);
+        out[2 * (size_t)i + 1] = make_uint4((uint32_t)count[al], 0u, 0u, 0u);
+    }
+};
+
+// shared beta term of the mixture: entry k is topic k
+struct BetaSrc {
+    const int32_t* __restrict__ nk;
+    double beta, betabar;
+    __device__ __forceinline__ uint64_t q0(int32_t k) const
+    {
+#pragma clang fp contract(off)
+        return quantise40(beta / ((double)nk[k] + betabar));
+    }
+};
+
+struct BetaSink {
+    uint2* __restrict__ out;
+    __device__ __forceinline__ void put(int32_t k, uint32_t split, uint32_t al) const
+    {
+        out[k] = make_uint2(split, al);
+    }
+};
+
+struct DenseArgs {
+    const int32_t* words;  // NULL: word = block index
+    int32_t n_words;
+    const int32_t* nkw;
+    const int32_t* nk;
+    int32_t K;
+    double beta, betabar;
+    uint4* alias;
+    uint32_t* cap;   // nullable
+    uint4* metaA;    // nullable
+    int32_t use_cache;
+    unsigned char* ws;  // GLOBAL: list memory, ws_stride bytes per workgroup
+    size_t ws_stride;
+};
+
+template <bool GLOBAL>
+__device__ __forceinline__ void dense_table(const DenseArgs& a, int32_t w, unsigned char* lists)
+{
+    const int32_t K = a.K;
+    const int32_t* row = a.nkw + (size_t)w * (size_t)K;
+    DenseSrc src{row, a.nk, a.beta, a.betabar};
+    DenseSink sink{a.alias + (size_t)w * (size_t)K, row};
+    uint64_t Q0;
+    uint32_t C;
+    build_alias_table<GLOBAL>(K, src, sink, lists, a.use_cache != 0, Q0, C);
+    if (threadIdx.x == 0) {
+        if (a.cap) a.cap[w] = C;
+        if (a.metaA) a.metaA[w] = make_uint4((uint32_t)K, C, 0u, 0u);
+    }
+}
+
+// one workgroup per word, lists in LDS
+__global__ __launch_bounds__(1024) void alias_dense_lds_kernel(DenseArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
-    // dx[0..A]   : Delta_a (exclusive deficit sums of the lights, dx[A] = total)
-    // dx[K-b]    : X_b     (inclusive excess sums of the heavies), b = 0..B-1, A + B = K
-    uint64_t* dx = reinterpret_cast<uint64_t*>(smem_raw);
-    uint32_t* hidx = reinterpret_cast<uint32_t*>(dx + (K + 1));  // hidx[b] = bin of heavy b
-    // qc[k] = q0_k saturated to 32 bits, kept for the later passes when LDS has room
-    // (0xFFFFFFFF: does not fit, recompute)
-    uint32_t* qc = hidx + K;
-    __shared__ uint64_t w_a[kMaxWaves], w_b[kMaxWaves];
-    __shared__ uint32_t w_c[kMaxWaves];
+    const int32_t w = a.words ? a.words[blockIdx.x] : (int32_t)blockIdx.x;
+    dense_table<false>(a, w, smem_raw);
+}
 
-    const int32_t w = blockIdx.x;
+// persistent workgroups, lists in a global workspace (K too large for LDS)
+__global__ __launch_bounds__(1024) void alias_dense_big_kernel(DenseArgs a)
+{
+    unsigned char* lists = a.ws + (size_t)blockIdx.x * a.ws_stride;
+    for (int32_t i = blockIdx.x; i < a.n_words; i += gridDim.x) {
+        const int32_t w = a.words ? a.words[i] : i;
+        dense_table<true>(a, w, lists);
+        ListMem<true>::barrier();
+    }
+}
+
+struct MixArgs {
+    const int32_t* words;
+    int32_t n_words;
+    const uint32_t* sp_off;
+    const int32_t* sp_topic;
+    const int32_t* sp_count;
+    const int32_t* sp_nnz;
+    const int32_t* nk;
+    double betabar;
+    uint4* ma;
+    uint4* metaA;
+    int32_t use_cache;
+    unsigned char* ws;
+    size_t ws_stride;
+};
+
+template <bool GLOBAL>
+__device__ __forceinline__ void mix_table(const MixArgs& a, int32_t w, unsigned char* lists)
+{
+    const int32_t n = a.sp_nnz[w];
+    if (n <= 0) {  // a word without tokens is never drawn from
+        if (threadIdx.x == 0) a.metaA[w] = make_uint4(0u, 0u, 0u, 0u);
+        return;
+    }
+    const size_t off = a.sp_off[w];
+    SparseSrc src{a.sp_topic + off, a.sp_count + off, a.nk, a.betabar};
+    SparseSink sink{a.ma + 2 * off, a.sp_topic + off, a.sp_count + off};
+    uint64_t QS;
+    uint32_t C;
+    build_alias_table<GLOBAL>(n, src, sink, lists, a.use_cache != 0, QS, C);
+    if (threadIdx.x == 0)
+        a.metaA[w] = make_uint4((uint32_t)n, C, (uint32_t)QS, (uint32_t)(QS >> 32));
+}
+
+__global__ __launch_bounds__(256) void alias_mix_lds_kernel(MixArgs a)
+{
+    extern __shared__ unsigned char smem_raw[];
+    mix_table<false>(a, a.words[blockIdx.x], smem_raw);
+}
+
+__global__ __launch_bounds__(1024) void alias_mix_big_kernel(MixArgs a)
+{
+    unsigned char* lists = a.ws + (size_t)blockIdx.x * a.ws_stride;
+    for (int32_t i = blockIdx.x; i < a.n_words; i += gridDim.x) {
+        mix_table<true>(a, a.words[i], lists);
+        ListMem<true>::barrier();
+    }
+}
+
+template <bool GLOBAL>
+__global__ __launch_bounds__(1024) void alias_beta_kernel(const int32_t* nk, int32_t K, double beta,
+                                                          double betabar, uint2* out,
+                                                          uint64_t* hdr, int32_t use_cache,
+                                                          unsigned char* ws)
+{
+    extern __shared__ unsigned char smem_raw[];
+    unsigned char* lists = GLOBAL ? ws : smem_raw;
+    BetaSrc src{nk, beta, betabar};
+    BetaSink sink{out};
+    uint64_t QB;
+    uint32_t C;
+    build_alias_table<GLOBAL>(K, src, sink, lists, use_cache != 0, QB, C);
+    if (threadIdx.x == 0) {
+        hdr[0] = QB;
+        hdr[1] = C;
+    }
+}
+
+// Non-zero topics of a dense row, ascending, into the word's list (a mixture word
+// that keeps a dense row).  One workgroup per word.
+__global__ __launch_bounds__(256) void compact_rows_kernel(const int32_t* __restrict__ words,
+                                                           const int32_t* __restrict__ nkw,
+                                                           int32_t K,
+                                                           const uint32_t* __restrict__ sp_off,
+                                                           int32_t* __restrict__ sp_topic,
+                                                           int32_t* __restrict__ sp_count,
+                                                           int32_t* __restrict__ sp_nnz)
+{
+    __shared__ uint32_t wcnt[4];
+    const int32_t w = words[blockIdx.x];
+    const int32_t* __restrict__ row = nkw + (size_t)w * (size_t)K;
+    const size_t off = sp_off[w];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
     const int nw = blockDim.x >> 6;
-    const int32_t* __restrict__ row = nkw + (size_t)w * (size_t)K;
-    uint4* __restrict__ out = alias + (size_t)w * (size_t)K;
-    const int32_t S = (((K + nw - 1) / nw + kWave - 1) / kWave) * kWave;  // bins per wave
-    const int32_t kb = wv * S;
-    const int32_t ke = (kb + S < K) ? kb + S : K;
-
-    // pass 1: Q0 and, for the usual case of no shift, Q
-    uint64_t p0 = 0, p1 = 0;
-#pragma unroll 4
-    for (int32_t k = kb + lane; k < ke; k += kWave) {
-        const uint64_t q0 = bin_q0(row, nk, k, beta, betabar);
-        if (use_cache) qc[k] = (q0 < 0xFFFFFFFFull) ? (uint32_t)q0 : 0xFFFFFFFFu;
-        p0 += q0;
-        p1 += (q0 < 1) ? 1 : q0;
-    }
-    p0 = wave_sum_u64(p0);
-    p1 = wave_sum_u64(p1);
-    if (lane == 0) { w_a[wv] = p0; w_b[wv] = p1; }
-    __syncthreads();
-    uint64_t Q0 = 0, Q = 0;
-    for (int i = 0; i < nw; ++i) { Q0 += w_a[i]; Q += w_b[i]; }
-    int sh = 0;
-    while ((Q0 >> sh) >= ((uint64_t)K << 31)) ++sh;
-    if (sh > 0) {  // uniform over the block
-        p1 = 0;
-        for (int32_t k = kb + lane; k < ke; k += kWave) {
-            uint64_t q = use_cache ? (uint64_t)qc[k] : 0xFFFFFFFFull;
-            if (q == 0xFFFFFFFFull) q = bin_q0(row, nk, k, beta, betabar);
-            q >>= sh;
-            p1 += (q < 1) ? 1 : q;
-        }
-        p1 = wave_sum_u64(p1);
+    uint32_t base = 0;
+    for (int32_t k0 = 0; k0 < K; k0 += (int32_t)blockDim.x) {
+        const int32_t k = k0 + (int32_t)threadIdx.x;
+        const int32_t v = (k < K) ? row[k] : 0;
+        const uint64_t mask = __ballot(v > 0);
         __syncthreads();
-        if (lane == 0) w_b[wv] = p1;
+        if (lane == 0) wcnt[wv] = (uint32_t)__popcll(mask);
         __syncthreads();
-        Q = 0;
-        for (int i = 0; i < nw; ++i) Q += w_b[i];
+        uint32_t before = 0, total = 0;
+        for (int i = 0; i < nw; ++i) {
+            if (i < wv) before += wcnt[i];
+            total += wcnt[i];
+        }
+        if (v > 0) {
+            const size_t p = off + base + before + rank_below(mask);
+            sp_topic[p] = k;
+            sp_count[p] = v;
+        }
+        base += total;
     }
-    const uint64_t C = (Q + (uint64_t)K - 1) / (uint64_t)K;
-    const uint64_t pad = (uint64_t)K * C - Q;
-    auto mass = [&](int32_t k) -> uint64_t {
-        uint64_t q = use_cache ? (uint64_t)qc[k] : 0xFFFFFFFFull;
-        if (q == 0xFFFFFFFFull) q = bin_q0(row, nk, k, beta, betabar);
-        q >>= sh;
-        if (q < 1) q = 1;
-        return q + (((uint64_t)k < pad) ? 1u : 0u);
-    };
+    if (threadIdx.x == 0) sp_nnz[w] = (int32_t)base;
+}
 
-    // pass 2: per-wave totals (lights, their deficit, the heavies' excess)
-    uint32_t lc = 0;
-    uint64_t df = 0, ex = 0;
-    for (int32_t k = kb + lane; k < ke; k += kWave) {
-        const uint64_t m = mass(k);
-        if (m < C) { lc += 1; df += C - m; } else { ex += m - C; }
-    }
-    df = wave_sum_u64(df);
-    ex = wave_sum_u64(ex);
-    lc = (uint32_t)wave_sum_u64(lc);
-    __syncthreads();  // w_a / w_b of pass 1 are no longer read
-    if (lane == 0) { w_a[wv] = df; w_b[wv] = ex; w_c[wv] = lc; }
-    __syncthreads();
-    uint32_t a_run = 0, A = 0;
-    uint64_t d_run = 0, x_run = 0, d_tot = 0;
-    for (int i = 0; i < nw; ++i) {
-        if (i < wv) { a_run += w_c[i]; d_run += w_a[i]; x_run += w_b[i]; }
-        A += w_c[i];
-        d_tot += w_a[i];
-    }
-    const uint32_t B = (uint32_t)K - A;
-    uint32_t b_run = (uint32_t)kb - a_run;
-    if (threadIdx.x == 0) {
-        dx[A] = d_tot;
-        cap[w] = (uint32_t)C;
-    }
-    const uint32_t a_wave = a_run, b_wave = b_run;
+template <class Kern>
+int set_lds(lda_ctx* c, Kern kern, size_t lds)
+{
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    return LDA_OK;
+}
 
-    // pass 3: the two ascending lists with their running sums
-    for (int32_t k0 = kb; k0 < ke; k0 += kWave) {
-        const int32_t k = k0 + lane;
-        const bool valid = k < ke;
-        const uint64_t m = valid ? mass(k) : C;
-        const bool light = valid && m < C;
-        const bool heavy = valid && !light;
-        const uint64_t lmask = __ballot(light);
-        const uint64_t dinc = wave_inclusive_scan_u64(light ? C - m : 0ull);
-        const uint64_t xinc = wave_inclusive_scan_u64(heavy ? m - C : 0ull);
-        const uint32_t la = rank_below(lmask);
-        if (light) {
-            dx[a_run + la] = d_run + dinc - (C - m);
-        } else if (heavy) {
-            const uint32_t b = b_run + ((uint32_t)lane - la);
-            dx[K - b] = x_run + xinc;
-            hidx[b] = (uint32_t)k;
-        }
-        const uint32_t nl = (uint32_t)__popcll(lmask);
-        const uint32_t nv = (uint32_t)((ke - k0 < kWave) ? ke - k0 : kWave);
-        a_run += nl;
-        b_run += nv - nl;
-        d_run += readlane_u64(dinc, kWave - 1);
-        x_run += readlane_u64(xinc, kWave - 1);
-    }
-    __syncthreads();
+constexpr size_t kLdsLimit = 160 * 1024 - 1024;  // 160 KiB per workgroup, room for statics
 
-    // pass 4: pair them.  Within a wave the ranks of one kind only grow and the
-    // partner index is monotone in the rank.  Per round the whole wave searches the
-    // partner of the last light (heavy) starting from the previous round's result;
-    // every lane then searches only between those two bounds.
-    a_run = a_wave;
-    b_run = b_wave;
-    uint32_t b_prev = 0;  // partner of the last light met so far
-    uint32_t a_prev = 0;  // partner of the last heavy met so far
-    for (int32_t k0 = kb; k0 < ke; k0 += kWave) {
-        const int32_t k = k0 + lane;
-        const bool valid = k < ke;
-        const uint64_t m = valid ? mass(k) : C;
-        const bool light = valid && m < C;
-        const bool heavy = valid && !light;
-        const uint64_t lmask = __ballot(light);
-        const uint64_t hmask = __ballot(heavy);
-        const uint32_t la = rank_below(lmask);
-        const uint32_t b_own = b_run + ((uint32_t)lane - la);
-        // own list entry: Delta_a of a light, X_b of a heavy
-        uint64_t own = 0;
-        if (light) own = dx[a_run + la];
-        if (heavy) own = dx[K - b_own];
-        uint32_t b_hi = b_prev, a_hi = a_prev;
-        if (lmask != 0) {  // uniform
-            const uint64_t delta_last = readlane_u64(own, 63 - __clzll((unsigned long long)lmask));
-            // first b with X_b > delta; X_{B-1} = total deficit > every delta
-            b_hi = wave_first_true(b_prev, B - 1, lane,
-                                   [&](uint32_t i) { return dx[K - i] > delta_last; });
-        }
-        if (hmask != 0) {  // uniform
-            const uint64_t x_last = readlane_u64(own, 63 - __clzll((unsigned long long)hmask));
-            // first a with Delta_a >= X; Delta_A = total excess >= every X
-            a_hi = wave_first_true(a_prev, A, lane, [&](uint32_t i) { return dx[i] >= x_last; });
-        }
-        uint32_t split = 0, al = 0;
-        if (light) {
-            uint32_t lo = b_prev, hi = b_hi;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (dx[K - mid] > own) hi = mid; else lo = mid + 1;
-            }
-            split = (uint32_t)m;
-            al = hidx[lo];
-        } else if (heavy) {
-            uint32_t lo = a_prev, hi = a_hi;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                if (dx[mid] >= own) hi = mid; else lo = mid + 1;
-            }
-            const uint64_t sp = C + own - dx[lo];
-            split = (uint32_t)sp;
-            al = (sp < C) ? hidx[b_own + 1] : (uint32_t)k;
-        }
-        // the bin also carries the counts of its two outcomes for the sweep's accept test
-        if (valid) out[k] = make_uint4(split, al, (uint32_t)row[k], (uint32_t)row[al]);
-        b_prev = b_hi;
-        a_prev = a_hi;
-        const uint32_t nl = (uint32_t)__popcll(lmask);
-        const uint32_t nv = (uint32_t)((ke - k0 < kWave) ? ke - k0 : kWave);
-        a_run += nl;
-        b_run += nv - nl;
-    }
+// LDS bytes and cache flag for a table of n entries
+void lds_plan(size_t n, size_t& bytes, int32_t& use_cache)
+{
+    use_cache = alias_list_bytes(n, true) <= kLdsLimit ? 1 : 0;
+    bytes = alias_list_bytes(n, use_cache != 0);
 }
 
 }  // namespace
 
+int max_lds_table_entries() { return 12 * 1024; }
 int max_alias_topics() { return 12 * 1024; }
 
+// all-dense mode: every word, lists in LDS
 int launch_alias_build(lda_ctx* c)
 {
     const int32_t K = c->K;
-    if (K > max_alias_topics())
-        return fail(c, LDA_ERR_UNSUPPORTED, "dense alias build supports K <= %d", max_alias_topics());
+    if (K > max_lds_table_entries())
+        return fail(c, LDA_ERR_UNSUPPORTED, "dense alias build in LDS supports K <= %d",
+                    max_lds_table_entries());
     int nw = (K + kWave - 1) / kWave;
     if (nw > kMaxWaves) nw = kMaxWaves;
-    size_t lds = sizeof(uint64_t) * ((size_t)K + 1) + sizeof(uint32_t) * (size_t)K;
-    // room for the 4-byte mass cache next to the lists?  (160 KiB of LDS per workgroup)
-    const size_t lds_limit = 160 * 1024 - 1024;
-    const int32_t use_cache = (lds + sizeof(uint32_t) * (size_t)K <= lds_limit) ? 1 : 0;
-    if (use_cache) lds += sizeof(uint32_t) * (size_t)K;
-    if (lds > 48 * 1024)
-        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(alias_dense_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(alias_dense_kernel, dim3(c->V), dim3(nw * kWave), lds, c->stream, c->d_nkw,
-                       c->d_nk, K, c->beta, c->betabar, c->d_alias, c->d_cap, use_cache);
+    size_t lds;
+    int32_t use_cache;
+    lds_plan((size_t)K, lds, use_cache);
+    int rc = set_lds(c, alias_dense_lds_kernel, lds);
+    if (rc != LDA_OK) return rc;
+    DenseArgs a{};
+    a.words = nullptr; a.n_words = c->V; a.nkw = c->d_nkw; a.nk = c->d_nk; a.K = K;
+    a.beta = c->beta; a.betabar = c->betabar; a.alias = c->d_alias; a.cap = c->d_cap;
+    a.metaA = nullptr; a.use_cache = use_cache;
+    hipLaunchKernelGGL(alias_dense_lds_kernel, dim3(c->V), dim3(nw * kWave), lds, c->stream, a);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
+
+// hybrid mode: beta table, dense tables of the head words, mixture tables of the rest
+int launch_alias_build_hybrid(lda_ctx* c)
+{
+    const int32_t K = c->K;
+    const int lds_max = max_lds_table_entries();
+    int rc;
+    if (c->n_mix > 0) {
+        if (K <= lds_max) {
+            size_t lds;
+            int32_t use_cache;
+            lds_plan((size_t)K, lds, use_cache);
+            rc = set_lds(c, alias_beta_kernel<false>, lds);
+            if (rc != LDA_OK) return rc;
+            int nw = (K + kWave - 1) / kWave;
+            if (nw > kMaxWaves) nw = kMaxWaves;
+            hipLaunchKernelGGL(alias_beta_kernel<false>, dim3(1), dim3(nw * kWave), lds, c->stream,
+                               c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr,
+                               use_cache, nullptr);
+        } else {
+            hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, c->stream, c->d_nk,
+                               K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
+                               c->d_big_ws);
+        }
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_compact > 0) {
+        hipLaunchKernelGGL(compact_rows_kernel, dim3(c->n_compact), dim3(256), 0, c->stream,
+                           c->d_compact_words, c->d_nkw, K, c->d_sp_off, c->d_sp_topic,
+                           c->d_sp_count, c->d_sp_nnz);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_dense_alias > 0) {
+        DenseArgs a{};
+        a.words = c->d_dense_alias_words; a.n_words = c->n_dense_alias; a.nkw = c->d_nkw;
+        a.nk = c->d_nk; a.K = K; a.beta = c->beta; a.betabar = c->betabar; a.alias = c->d_alias;
+        a.cap = nullptr; a.metaA = c->d_metaA;
+        if (K <= lds_max) {
+            size_t lds;
+            lds_plan((size_t)K, lds, a.use_cache);
+            rc = set_lds(c, alias_dense_lds_kernel, lds);
+            if (rc != LDA_OK) return rc;
+            int nw = (K + kWave - 1) / kWave;
+            if (nw > kMaxWaves) nw = kMaxWaves;
+            hipLaunchKernelGGL(alias_dense_lds_kernel, dim3(c->n_dense_alias), dim3(nw * kWave), lds,
+                               c->stream, a);
+        } else {
+            a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
+            const int grid = c->n_dense_alias < c->n_big_wg ? c->n_dense_alias : c->n_big_wg;
+            hipLaunchKernelGGL(alias_dense_big_kernel, dim3(grid), dim3(1024), 0, c->stream, a);
+        }
+        LDA_HIP(c, hipGetLastError());
+    }
+    return LDA_OK;
+}
+
+// Mixture tables of the words in `words` whose list capacity is at most cap_entries
+// (cap_entries = 0: any size, built in the global workspace).
+int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries)
+{
+    if (n_words <= 0) return LDA_OK;
+    MixArgs a{};
+    a.words = words; a.n_words = n_words; a.sp_off = c->d_sp_off; a.sp_topic = c->d_sp_topic;
+    a.sp_count = c->d_sp_count; a.sp_nnz = c->d_sp_nnz; a.nk = c->d_nk; a.betabar = c->betabar;
+    a.ma = c->d_ma; a.metaA = c->d_metaA;
+    if (cap_entries > 0) {
+        size_t lds;
+        lds_plan((size_t)cap_entries, lds, a.use_cache);
+        int rc = set_lds(c, alias_mix_lds_kernel, lds);
+        if (rc != LDA_OK) return rc;
+        int threads = ((cap_entries + kWave - 1) / kWave) * kWave;
+        if (threads > 256) threads = 256;
+        hipLaunchKernelGGL(alias_mix_lds_kernel, dim3(n_words), dim3(threads), lds, c->stream, a);
+    } else {
+        a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
+        const int grid = n_words < c->n_big_wg ? n_words : c->n_big_wg;
+        hipLaunchKernelGGL(alias_mix_big_kernel, dim3(grid), dim3(1024), 0, c->stream, a);
+    }
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }

@@ -27,6 +27,11 @@ int fail(lda_ctx* c, int code, const char* fmt, ...)
 
 namespace {
 
+// bytes of list memory of the alias builder for n entries with the mass cache
+size_t alias_list_bytes_host(size_t n) { return 8 * (n + 1) + 4 * n + 4 * n; }
+
+int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff);
+
 template <class T>
 int dev_alloc(lda_ctx* c, T** p, size_t count, const char* what)
 {
@@ -57,7 +62,154 @@ void free_all(lda_ctx* c)
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
     dev_free(c->d_flag);
+    dev_free(c->d_wkind); dev_free(c->d_dense_alias_words); dev_free(c->d_mix_words);
+    for (int i = 0; i < 5; ++i) dev_free(c->d_mix_class[i]);
+    for (int i = 0; i < 4; ++i) dev_free(c->d_sortsp_class[i]);
+    dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
+    dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
+    dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); dev_free(c->d_metaB);
+    dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
+    dev_free(c->d_big_list); dev_free(c->d_scratch_rows); dev_free(c->d_bigsp_words);
 }
+
+template <class T>
+int upload(lda_ctx* c, T** dst, const std::vector<T>& v, const char* what)
+{
+    int rc = dev_alloc(c, dst, v.size(), what);
+    if (rc != LDA_OK) return rc;
+    if (!v.empty()) {
+        hipError_t e = hipMemcpy(*dst, v.data(), sizeof(T) * v.size(), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return fail(c, LDA_ERR_HIP, "upload of %s: %s", what, hipGetErrorString(e));
+    }
+    return LDA_OK;
+}
+
+// Word classes, list / hash-row offsets, work lists and buffers of the hybrid store.
+// woff: host copy of the word segment offsets.
+int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
+{
+    const int32_t V = c->V, K = c->K, H = c->H;
+    const int32_t min_count = c->opt.dense_alias_min_count;
+    c->h_wcount.resize(V);
+    c->h_wkind.resize(V);
+    c->h_sp_off.assign((size_t)V + 1, 0);
+    c->h_hs_off.assign((size_t)V + 1, 0);
+    std::vector<int32_t> dense_alias, mix, sparse, compact, bigsp, mixc[5], sortc[4];
+    std::vector<uint4> metaB(V);
+    static const int32_t mix_cap[4] = {64, 512, 4096, 0};
+    static const int32_t sort_cap[4] = {64, 512, 4096, 16384};
+    const int32_t lds_max = max_lds_table_entries();
+    uint64_t list_total = 0, hash_total = 0;
+    for (int32_t w = 0; w < V; ++w) {
+        const int32_t cw = woff[w + 1] - woff[w];
+        c->h_wcount[w] = cw;
+        const bool dense_row = w < H;
+        const bool dense_alias_w = (min_count == 0) || (cw >= min_count);
+        if (dense_alias_w && !dense_row)
+            return fail(c, LDA_ERR_ARG,
+                        "lda_init: word %d (count %d) would draw from a dense table but has no dense "
+                        "row; raise dense_alias_min_count or dense_rows", w, cw);
+        const uint8_t kind = (dense_row ? 1 : 0) | (dense_alias_w ? 2 : 0);
+        c->h_wkind[w] = kind;
+        c->h_sp_off[w] = (uint32_t)list_total;
+        c->h_hs_off[w] = (uint32_t)hash_total;
+        uint32_t lg = 0;
+        if (dense_alias_w) {
+            dense_alias.push_back(w);
+        } else {
+            const int32_t cap = std::min(cw, K);
+            list_total += (uint64_t)cap;
+            mix.push_back(w);
+            int cl = 4;
+            if (cap <= mix_cap[0]) cl = 0;
+            else if (cap <= mix_cap[1]) cl = 1;
+            else if (cap <= mix_cap[2]) cl = 2;
+            else if (cap <= lds_max) cl = 3;
+            mixc[cl].push_back(w);
+            if (dense_row) {
+                compact.push_back(w);
+            } else {
+                sparse.push_back(w);
+                uint32_t hcap = 2;
+                while (hcap < 2u * (uint32_t)cap) hcap <<= 1;
+                while ((1u << lg) < hcap) ++lg;
+                hash_total += hcap;
+                if (cw <= sort_cap[3]) {
+                    int sc = 3;
+                    for (int i = 0; i < 4; ++i) if (cw <= sort_cap[i]) { sc = i; break; }
+                    sortc[sc].push_back(w);
+                } else {
+                    bigsp.push_back(w);
+                }
+            }
+        }
+        metaB[w] = make_uint4(c->h_sp_off[w], c->h_hs_off[w], lg, kind);
+        if (list_total > 0x7FFFFFFFull || hash_total > 0xFFFFFFFFull)
+            return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: sparse rows exceed 2^31 entries");
+    }
+    c->h_sp_off[V] = (uint32_t)list_total;
+    c->h_hs_off[V] = (uint32_t)hash_total;
+    c->total_list = (int64_t)list_total;
+    c->total_hash = (int64_t)hash_total;
+    c->n_dense_alias = (int32_t)dense_alias.size();
+    c->n_mix = (int32_t)mix.size();
+    c->n_sparse = (int32_t)sparse.size();
+    c->n_compact = (int32_t)compact.size();
+    c->n_bigsp = (int32_t)bigsp.size();
+    if (c->n_dense_alias > 0 && K > lds_max && (double)H * (double)K > 4.0e9)
+        return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: dense tables for %d words at K = %d", H, K);
+
+    int rc;
+#define UP(field, vec, what) do { rc = upload(c, &c->field, vec, what); if (rc != LDA_OK) return rc; } while (0)
+    UP(d_wkind, c->h_wkind, "word classes");
+    UP(d_dense_alias_words, dense_alias, "dense-table words");
+    UP(d_mix_words, mix, "mixture words");
+    UP(d_sparse_words, sparse, "sparse-row words");
+    UP(d_compact_words, compact, "compaction words");
+    UP(d_bigsp_words, bigsp, "big sparse words");
+    for (int i = 0; i < 5; ++i) {
+        c->n_mix_class[i] = (int32_t)mixc[i].size();
+        UP(d_mix_class[i], mixc[i], "mixture class");
+    }
+    for (int i = 0; i < 4; ++i) {
+        c->n_sortsp_class[i] = (int32_t)sortc[i].size();
+        UP(d_sortsp_class[i], sortc[i], "sort class");
+    }
+    UP(d_sp_off, c->h_sp_off, "list offsets");
+    UP(d_hs_off, c->h_hs_off, "hash offsets");
+    UP(d_metaB, metaB, "word descriptors");
+#undef UP
+#define AL(field, count, what) do { rc = dev_alloc(c, &c->field, (size_t)(count), what); if (rc != LDA_OK) return rc; } while (0)
+    AL(d_metaA, V, "word tables");
+    AL(d_sp_topic, list_total, "sparse rows");
+    AL(d_sp_count, list_total, "sparse rows");
+    AL(d_sp_nnz, V, "sparse rows");
+    AL(d_hs, hash_total, "hash rows");
+    AL(d_ma, 2 * list_total, "mixture tables");
+    AL(d_beta_alias, K, "beta table");
+    AL(d_beta_hdr, 2, "beta table");
+    LDA_HIP(c, hipMemsetAsync(c->d_metaA, 0, sizeof(uint4) * (size_t)V, c->stream));
+    LDA_HIP(c, hipMemsetAsync(c->d_sp_nnz, 0, sizeof(int32_t) * (size_t)V, c->stream));
+    // global list memory for tables too large for LDS
+    const bool need_big = (K > lds_max && (c->n_dense_alias > 0 || c->n_mix > 0)) ||
+                          c->n_mix_class[4] > 0;
+    if (need_big) {
+        c->big_ws_stride = (alias_list_bytes_host((size_t)K) + 255) / 256 * 256;
+        int64_t wg = (int64_t)(2.0e9 / (double)c->big_ws_stride);
+        c->n_big_wg = (int32_t)std::max<int64_t>(1, std::min<int64_t>(256, wg));
+        AL(d_big_ws, c->big_ws_stride * (size_t)c->n_big_wg, "table workspace");
+    }
+    if (c->n_bigsp > 0) {
+        int64_t rows = (int64_t)(1.0e9 / (4.0 * (double)K));
+        c->n_scratch_rows = (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, rows));
+        AL(d_scratch_rows, (size_t)c->n_scratch_rows * (size_t)K, "scratch rows");
+        LDA_HIP(c, hipMemsetAsync(c->d_scratch_rows, 0,
+                                  sizeof(int32_t) * (size_t)c->n_scratch_rows * (size_t)K, c->stream));
+    }
+#undef AL
+    return LDA_OK;
+}
+
 
 // Greedy tiling of the documents: consecutive documents are grouped while they
 // fit cap_tokens tokens and cap_docs documents.  A document longer than
@@ -120,21 +272,23 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (opt) o = *opt;
     if (o.proposal_mode < 0 || o.proposal_mode > 2)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: proposal_mode must be 0, 1 or 2");
-    if (o.dense_rows < 0 || o.dense_alias_min_count < 0 || o.sweep_chunk_tokens < 0 ||
+    if (o.dense_rows < -1 || o.dense_alias_min_count < 0 || o.sweep_chunk_tokens < 0 ||
         o.sweep_block_threads < 0 || o.rebuild_tile_tokens < 0)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: negative option");
     for (int i = 0; i < 9; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
-    if (o.dense_rows != 0 || o.dense_alias_min_count != 0)
-        return fail(nullptr, LDA_ERR_UNSUPPORTED,
-                    "lda_init: hybrid rows / mixture proposal are not available in this build");
+    const bool hybrid = (o.dense_rows != 0) || (o.dense_alias_min_count != 0);
+    const int32_t H = o.dense_rows < 0 ? 0 : (o.dense_rows == 0 ? V : std::min(o.dense_rows, V));
     if (K > kMaxPackedTopics)
-        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K must be < 2^20");
-    if (K > max_alias_topics() || K > max_rebuild_topics())
-        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K = %d exceeds the dense-path limit %d",
-                    K, std::min(max_alias_topics(), max_rebuild_topics()));
-    if ((double)V * (double)K > 4.0e10)
-        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: dense V*K too large");
+        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K must be < 2^20 - 1");
+    if (!hybrid && (K > max_alias_topics() || K > max_rebuild_topics()))
+        return fail(nullptr, LDA_ERR_UNSUPPORTED,
+                    "lda_init: K = %d exceeds the all-dense limit %d; use the hybrid store "
+                    "(dense_rows, dense_alias_min_count)", K,
+                    std::min(max_alias_topics(), max_rebuild_topics()));
+    if ((double)H * (double)K > 1.0e10)
+        return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: %d dense rows of %d topics are too large",
+                    H, K);
 
     lda_ctx* c = new (std::nothrow) lda_ctx();
     if (!c) return fail(nullptr, LDA_ERR_OOM, "lda_init: host allocation failed");
@@ -144,6 +298,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     c->betabar = (double)V * beta;
     c->seed = seed;
     c->opt = o;
+    c->hybrid = hybrid;
+    c->H = H;
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
 
     // sweep tiling parameters (LDS: 12 bytes per token + 4 per document).  A packed n_kd
@@ -185,7 +341,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     }
     c->long_slots = long_slot[c->n_long];
 
-    const size_t VK = (size_t)V * (size_t)K;
+    const size_t VK = (size_t)H * (size_t)K;  // dense rows (all V of them in the all-dense mode)
+    bool any_dense_alias = true;  // refined below in the hybrid mode
 #define TRY(x) do { rc = (x); if (rc != LDA_OK) return bail(rc); } while (0)
 #define TRY_HIP(call)                                                                     \
     do {                                                                                  \
@@ -201,7 +358,6 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_woff, (size_t)V + 1, "word offsets"));
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
     TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));
-    TRY(dev_alloc(c, &c->d_alias, VK, "alias tables"));
     TRY(dev_alloc(c, &c->d_cap, (size_t)V, "alias capacities"));
     TRY(dev_alloc(c, &c->d_chunk_doc, chunk_doc.size(), "document tiles"));
     TRY(dev_alloc(c, &c->d_tokdoc, (size_t)N, "token document indices"));
@@ -238,10 +394,15 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     std::vector<int32_t> woff((size_t)V + 1);
     TRY_HIP(hipMemcpy(woff.data(), c->d_woff, sizeof(int32_t) * ((size_t)V + 1),
                       hipMemcpyDeviceToHost));
+    if (hybrid) {
+        TRY(setup_hybrid(c, woff));
+        any_dense_alias = c->n_dense_alias > 0;
+    }
+    TRY(dev_alloc(c, &c->d_alias, any_dense_alias ? VK : 1, "alias tables"));
     std::vector<RebuildTile> tiles;
     std::vector<int32_t> multi;
-    tiles.reserve((size_t)V + 1024);
-    for (int32_t w = 0; w < V; ++w) {
+    tiles.reserve((size_t)H + 1024);
+    for (int32_t w = 0; w < H; ++w) {
         const int32_t b = woff[w], e = woff[w + 1];
         if (e - b <= tile_tokens) {
             tiles.push_back(RebuildTile{w, b, e, 0});
@@ -261,7 +422,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         TRY_HIP(hipMemcpy(c->d_multi_words, multi.data(), sizeof(int32_t) * multi.size(),
                           hipMemcpyHostToDevice));
 
-    TRY(launch_rebuild(c));
+    TRY(hybrid ? launch_rebuild_hybrid(c) : launch_rebuild(c));
     TRY_HIP(hipStreamSynchronize(c->stream));
 #undef TRY
 #undef TRY_HIP
@@ -276,7 +437,16 @@ int lda_build_alias(lda_ctx* c)
     if (!c) return LDA_ERR_ARG;
     if (c->state != COUNTS_VALID && c->state != ALIAS_VALID)
         return fail(c, LDA_ERR_STATE, "lda_build_alias: counts are stale (call lda_rebuild_counts)");
-    const int rc = launch_alias_build(c);
+    int rc;
+    if (c->hybrid) {
+        static const int32_t cap[5] = {64, 512, 4096, 0, 0};
+        rc = launch_alias_build_hybrid(c);
+        for (int cl = 0; cl < 5 && rc == LDA_OK; ++cl)
+            rc = launch_alias_mix_class(c, c->d_mix_class[cl], c->n_mix_class[cl],
+                                        cl == 3 ? max_lds_table_entries() : cap[cl]);
+    } else {
+        rc = launch_alias_build(c);
+    }
     if (rc == LDA_OK) c->state = ALIAS_VALID;
     return rc;
 }
@@ -288,7 +458,7 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
     if (c->state != ALIAS_VALID)
         return fail(c, LDA_ERR_STATE, "lda_sweep: needs fresh alias tables (call lda_build_alias)");
     if (c->sweep_index == 0xFFFFFFFEu) return fail(c, LDA_ERR_STATE, "lda_sweep: sweep index exhausted");
-    const int rc = launch_sweep(c, mh_steps);
+    const int rc = c->hybrid ? launch_sweep_hybrid(c, mh_steps) : launch_sweep(c, mh_steps);
     if (rc != LDA_OK) return rc;
     std::swap(c->d_z, c->d_znew);
     c->sweep_index += 1;
@@ -299,7 +469,7 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
 int lda_rebuild_counts(lda_ctx* c)
 {
     if (!c) return LDA_ERR_ARG;
-    const int rc = launch_rebuild(c);
+    const int rc = c->hybrid ? launch_rebuild_hybrid(c) : launch_rebuild(c);
     if (rc == LDA_OK) c->state = COUNTS_VALID;
     return rc;
 }
@@ -367,6 +537,22 @@ int lda_get_nkw_row(lda_ctx* c, int32_t w, int32_t* row)
     if (!c) return LDA_ERR_ARG;
     if (!row || w < 0 || w >= c->V) return fail(c, LDA_ERR_ARG, "lda_get_nkw_row: bad argument");
     if (c->state == SWEPT) return fail(c, LDA_ERR_STATE, "lda_get_nkw_row: counts are stale");
+    if (c->hybrid && !(c->h_wkind[w] & 1)) {  // sparse row: densify its list
+        int32_t nnz = 0;
+        LDA_HIP(c, hipMemcpyAsync(&nnz, c->d_sp_nnz + w, sizeof(int32_t), hipMemcpyDeviceToHost,
+                                  c->stream));
+        LDA_HIP(c, hipStreamSynchronize(c->stream));
+        std::vector<int32_t> t((size_t)nnz), n((size_t)nnz);
+        if (nnz > 0) {
+            LDA_HIP(c, hipMemcpy(t.data(), c->d_sp_topic + c->h_sp_off[w], sizeof(int32_t) * nnz,
+                                 hipMemcpyDeviceToHost));
+            LDA_HIP(c, hipMemcpy(n.data(), c->d_sp_count + c->h_sp_off[w], sizeof(int32_t) * nnz,
+                                 hipMemcpyDeviceToHost));
+        }
+        memset(row, 0, sizeof(int32_t) * (size_t)c->K);
+        for (int32_t i = 0; i < nnz; ++i) row[t[i]] = n[i];
+        return LDA_OK;
+    }
     LDA_HIP(c, hipMemcpyAsync(row, c->d_nkw + (size_t)w * (size_t)c->K,
                               sizeof(int32_t) * (size_t)c->K, hipMemcpyDeviceToHost, c->stream));
     LDA_HIP(c, hipStreamSynchronize(c->stream));
@@ -391,15 +577,74 @@ int lda_get_alias_row(lda_ctx* c, int32_t w, uint32_t* split, uint32_t* alias, u
     if (!split || !alias || !cap || w < 0 || w >= c->V)
         return fail(c, LDA_ERR_ARG, "lda_get_alias_row: bad argument");
     if (c->state != ALIAS_VALID) return fail(c, LDA_ERR_STATE, "lda_get_alias_row: no valid tables");
+    if (c->hybrid && !(c->h_wkind[w] & 2))
+        return fail(c, LDA_ERR_ARG, "lda_get_alias_row: word %d draws from the mixture", w);
     std::vector<uint4> h((size_t)c->K);
     LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_alias + (size_t)w * (size_t)c->K,
                               sizeof(uint4) * (size_t)c->K, hipMemcpyDeviceToHost, c->stream));
-    LDA_HIP(c, hipMemcpyAsync(cap, c->d_cap + w, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream));
+    if (c->hybrid) {
+        uint4 m;
+        LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
+        LDA_HIP(c, hipStreamSynchronize(c->stream));
+        *cap = m.y;
+    } else {
+        LDA_HIP(c, hipMemcpyAsync(cap, c->d_cap + w, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                  c->stream));
+    }
     LDA_HIP(c, hipStreamSynchronize(c->stream));
     for (int32_t k = 0; k < c->K; ++k) {
         split[k] = h[k].x;
         alias[k] = h[k].y;
     }
+    return LDA_OK;
+}
+
+int lda_get_sparse_table(lda_ctx* c, int32_t w, int32_t cap_entries, int32_t* n, int32_t* topics,
+                         uint32_t* split, int32_t* alias_topic, uint32_t* cap, uint64_t* mass)
+{
+    if (!c) return LDA_ERR_ARG;
+    if (!n || w < 0 || w >= c->V || cap_entries < 0)
+        return fail(c, LDA_ERR_ARG, "lda_get_sparse_table: bad argument");
+    if (c->state != ALIAS_VALID) return fail(c, LDA_ERR_STATE, "lda_get_sparse_table: no valid tables");
+    if (!c->hybrid || (c->h_wkind[w] & 2))
+        return fail(c, LDA_ERR_ARG, "lda_get_sparse_table: word %d draws from a dense table", w);
+    uint4 m;
+    LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
+    LDA_HIP(c, hipStreamSynchronize(c->stream));
+    *n = (int32_t)m.x;
+    if (cap) *cap = m.y;
+    if (mass) *mass = ((uint64_t)m.w << 32) | m.z;
+    if ((int32_t)m.x <= cap_entries && m.x > 0 && topics && split && alias_topic) {
+        std::vector<uint4> e(2 * (size_t)m.x);
+        LDA_HIP(c, hipMemcpy(e.data(), c->d_ma + 2 * (size_t)c->h_sp_off[w],
+                             sizeof(uint4) * e.size(), hipMemcpyDeviceToHost));
+        for (uint32_t i = 0; i < m.x; ++i) {
+            split[i] = e[2 * i].x;
+            topics[i] = (int32_t)e[2 * i].y;
+            alias_topic[i] = (int32_t)e[2 * i].z;
+        }
+    }
+    return LDA_OK;
+}
+
+int lda_get_beta_table(lda_ctx* c, uint32_t* split, uint32_t* alias, uint32_t* cap, uint64_t* mass)
+{
+    if (!c) return LDA_ERR_ARG;
+    if (!split || !alias || !cap || !mass) return fail(c, LDA_ERR_ARG, "lda_get_beta_table: NULL buffer");
+    if (c->state != ALIAS_VALID || !c->hybrid || c->n_mix == 0)
+        return fail(c, LDA_ERR_STATE, "lda_get_beta_table: no mixture tables");
+    std::vector<uint2> e((size_t)c->K);
+    uint64_t hdr[2];
+    LDA_HIP(c, hipMemcpyAsync(e.data(), c->d_beta_alias, sizeof(uint2) * (size_t)c->K,
+                              hipMemcpyDeviceToHost, c->stream));
+    LDA_HIP(c, hipMemcpyAsync(hdr, c->d_beta_hdr, sizeof(hdr), hipMemcpyDeviceToHost, c->stream));
+    LDA_HIP(c, hipStreamSynchronize(c->stream));
+    for (int32_t k = 0; k < c->K; ++k) {
+        split[k] = e[k].x;
+        alias[k] = e[k].y;
+    }
+    *mass = hdr[0];
+    *cap = (uint32_t)hdr[1];
     return LDA_OK;
 }
 

@@ -71,6 +71,47 @@ struct lda_ctx {
     int32_t n_tiles = 0;
     int32_t* d_multi_words = nullptr;  // words that own several tiles
     int32_t n_multi_words = 0;
+    // hybrid store / mixture proposal (Sec. 4.2 and 5); all null in the all-dense mode
+    bool hybrid = false;
+    int32_t H = 0;                       // word ids [0, H) own a dense n_kw row
+    uint8_t* d_wkind = nullptr;          // [V] bit 0: dense row, bit 1: dense proposal table
+    int32_t* d_dense_alias_words = nullptr;  // words that draw from a dense K-bin table
+    int32_t n_dense_alias = 0;
+    int32_t* d_mix_words = nullptr;      // words that draw from the mixture
+    int32_t n_mix = 0;
+    // the mixture words by list capacity: <= 64, <= 512, <= 4096, <= LDS maximum, larger
+    int32_t* d_mix_class[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    int32_t n_mix_class[5] = {0, 0, 0, 0, 0};
+    int32_t* d_sparse_words = nullptr;   // words with a sparse row (subset of the mixture words)
+    int32_t n_sparse = 0;
+    int32_t* d_compact_words = nullptr;  // mixture words with a dense row (list made by compaction)
+    int32_t n_compact = 0;
+    uint32_t* d_sp_off = nullptr;        // [V+1] first list entry of word w (capacity min(c_w, K))
+    int32_t* d_sp_topic = nullptr;       // non-zero topics of the word, ascending
+    int32_t* d_sp_count = nullptr;       // their counts
+    int32_t* d_sp_nnz = nullptr;         // [V] entries in use
+    uint32_t* d_hs_off = nullptr;        // [V+1] first hash slot of word w (power-of-two capacity)
+    uint2* d_hs = nullptr;               // (topic, count) slots, topic = -1: empty
+    uint4* d_ma = nullptr;               // mixture tables: two uint4 per list entry
+    uint4* d_metaA = nullptr;            // [V] (entries n, capacity C, QS low, QS high)
+    uint4* d_metaB = nullptr;            // [V] (list offset, hash offset, hash mask, kind)
+    uint2* d_beta_alias = nullptr;       // [K] shared table of the beta term (split, alias)
+    uint64_t* d_beta_hdr = nullptr;      // [2] QB, capacity
+    unsigned char* d_big_ws = nullptr;   // list memory of the workgroups that build big tables
+    size_t big_ws_stride = 0;
+    int32_t n_big_wg = 0;
+    int32_t* d_big_list = nullptr;       // [n_mix + 1] mixture words too big for LDS, [0] = count
+    int32_t* d_scratch_rows = nullptr;   // dense scratch rows for the rebuild of big sparse words
+    int32_t n_scratch_rows = 0;
+    int32_t* d_bigsp_words = nullptr;    // sparse-row words rebuilt through scratch rows
+    int32_t n_bigsp = 0;
+    // sparse-row words rebuilt by an LDS sort, by token count: <= 64, <= 512, <= 4096, <= 16384
+    int32_t* d_sortsp_class[4] = {nullptr, nullptr, nullptr, nullptr};
+    int32_t n_sortsp_class[4] = {0, 0, 0, 0};
+    int64_t total_list = 0, total_hash = 0;
+    std::vector<int32_t> h_wcount;       // corpus frequency of every word
+    std::vector<uint8_t> h_wkind;
+    std::vector<uint32_t> h_sp_off, h_hs_off;
     // scratch
     double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
     int32_t n_partial = 0;
@@ -96,6 +137,18 @@ void set_init_error(const char* msg);
 // launchers implemented in the kernel files
 int launch_layout(lda_ctx* c, const int32_t* h_word);      // word-major order, woff, z init
 int launch_alias_build(lda_ctx* c);
+int launch_alias_build_hybrid(lda_ctx* c);
+int launch_rebuild_hybrid(lda_ctx* c);
+int launch_sweep_hybrid(lda_ctx* c, int32_t mh_steps);
+int launch_loglik_word_hybrid(lda_ctx* c, double* word_part);
+int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries);
+int max_lds_table_entries();  // largest alias table built in LDS
+
+// slot of topic t in a hash row of 2^lg slots (multiplicative hashing, top bits)
+__host__ __device__ inline uint32_t row_hash_slot(int32_t t, uint32_t lg)
+{
+    return ((uint32_t)t * 0x9E3779B1u) >> (32u - lg);
+}
 int launch_sweep(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);

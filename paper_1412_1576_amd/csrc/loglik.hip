@@ -100,6 +100,30 @@ __global__ __launch_bounds__(256) void loglik_nk_kernel(const int32_t* __restric
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
+// word part over the sparse rows: one wave per word of the list, grid-stride
+__global__ __launch_bounds__(256) void loglik_sparse_kernel(const int32_t* __restrict__ words,
+                                                            int32_t n_words,
+                                                            const uint32_t* __restrict__ sp_off,
+                                                            const int32_t* __restrict__ sp_count,
+                                                            const int32_t* __restrict__ sp_nnz,
+                                                            double beta, double lg_beta,
+                                                            double* __restrict__ partial)
+{
+    __shared__ double wtot[4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    double acc = 0.0;
+    for (int32_t i = wave; i < n_words; i += nwaves) {
+        const int32_t w = words[i];
+        const int32_t nnz = sp_nnz[w];
+        const int32_t* __restrict__ cnt = sp_count + sp_off[w];
+        for (int32_t e = lane; e < nnz; e += kWave) acc += lgamma((double)cnt[e] + beta) - lg_beta;
+    }
+    const double s = block_sum_f64(acc, wtot);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
 // compensated (Neumaier) sum of the partials in index order
 double host_sum(const std::vector<double>& v, size_t n)
 {
@@ -147,13 +171,26 @@ int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
     }
     {
         const int blocks = 4096;
-        hipLaunchKernelGGL(loglik_word_kernel, dim3(blocks), dim3(256), 0, c->stream, c->d_nkw,
-                           (int64_t)c->V * (int64_t)c->K, c->beta, lgb, c->d_partial);
-        LDA_HIP(c, hipGetLastError());
-        LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * blocks,
-                                  hipMemcpyDeviceToHost, c->stream));
-        LDA_HIP(c, hipStreamSynchronize(c->stream));
-        word += host_sum(h, blocks);
+        const int64_t dense_rows = c->hybrid ? c->H : c->V;
+        if (dense_rows > 0) {
+            hipLaunchKernelGGL(loglik_word_kernel, dim3(blocks), dim3(256), 0, c->stream, c->d_nkw,
+                               dense_rows * (int64_t)c->K, c->beta, lgb, c->d_partial);
+            LDA_HIP(c, hipGetLastError());
+            LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * blocks,
+                                      hipMemcpyDeviceToHost, c->stream));
+            LDA_HIP(c, hipStreamSynchronize(c->stream));
+            word += host_sum(h, blocks);
+        }
+        if (c->hybrid && c->n_sparse > 0) {
+            hipLaunchKernelGGL(loglik_sparse_kernel, dim3(blocks), dim3(256), 0, c->stream,
+                               c->d_sparse_words, c->n_sparse, c->d_sp_off, c->d_sp_count,
+                               c->d_sp_nnz, c->beta, lgb, c->d_partial);
+            LDA_HIP(c, hipGetLastError());
+            LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * blocks,
+                                      hipMemcpyDeviceToHost, c->stream));
+            LDA_HIP(c, hipStreamSynchronize(c->stream));
+            word += host_sum(h, blocks);
+        }
         const int kb = 64;
         hipLaunchKernelGGL(loglik_nk_kernel, dim3(kb), dim3(256), 0, c->stream, c->d_nk, c->K,
                            c->betabar, lgbb, c->d_partial);

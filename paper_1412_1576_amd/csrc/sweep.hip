@@ -30,6 +30,13 @@ struct SweepArgs {
     int32_t cap_tokens;
     double alpha, beta, alphabar, betabar;
     uint32_t seed_lo, seed_hi, sweep;
+    // hybrid store / mixture proposal (null in the all-dense mode)
+    const uint4* metaA;       // (entries n, capacity C, QS low, QS high) per word
+    const uint4* metaB;       // (list offset, hash offset, log2 hash slots, kind) per word
+    const uint4* ma;          // mixture bins, two uint4 per list entry
+    const uint2* hs;          // hash rows (topic, count)
+    const uint2* beta_alias;  // shared beta-term table
+    const uint64_t* beta_hdr; // QB, capacity
     // long documents
     const int32_t* long_doc;
     const int64_t* long_slot;
@@ -167,9 +174,145 @@ __device__ __forceinline__ void mh_chains(const SweepArgs& A, const DocView (&do
     }
 }
 
+// ---- hybrid store: the word side of a token ------------------------------------------
+struct WordView {
+    uint32_t kind;   // bit 0: dense n_kw row, bit 1: dense proposal table
+    uint32_t n, C;   // entries and capacity of the word's own table
+    uint64_t QS;     // integer mass of the sparse term (mixture form)
+    uint32_t list_off, hs_off, lg;
+    size_t wk;       // w * K (dense row / dense table offset)
+};
+
+__device__ __forceinline__ WordView load_word(const SweepArgs& A, int32_t w)
+{
+    const uint4 a = A.metaA[w], b = A.metaB[w];
+    WordView v;
+    v.n = a.x; v.C = a.y; v.QS = ((uint64_t)a.w << 32) | a.z;
+    v.list_off = b.x; v.hs_off = b.y; v.lg = b.z; v.kind = b.w;
+    v.wk = (size_t)w * (size_t)A.K;
+    return v;
+}
+
+// n_kw[w][t]: dense row, or the word's hash row (Sec. 5)
+__device__ __forceinline__ int32_t nkw_lookup(const SweepArgs& A, const WordView& v, int32_t t)
+{
+    if (v.kind & 1u) return A.nkw[v.wk + (size_t)t];
+    const uint2* __restrict__ row = A.hs + v.hs_off;
+    const uint32_t mask = (1u << v.lg) - 1u;
+    uint32_t s = row_hash_slot(t, v.lg);
+    for (uint32_t i = 0; i <= mask; ++i) {
+        const uint2 e = row[s];
+        if (e.x == (uint32_t)t) return (int32_t)e.y;
+        if (e.x == 0xFFFFFFFFu) return 0;
+        s = (s + 1) & mask;
+    }
+    return 0;
+}
+
+// Chains with the hybrid word side: dense tables for the head words, the
+// sparsified mixture (Sec. 4.2) for the others.  Same structure as mh_chains.
+template <int T, class DocView>
+__device__ __forceinline__ void mh_chains_hybrid(const SweepArgs& A, const DocView (&doc)[T],
+                                                 const uint32_t (&own)[T], const int32_t (&w)[T],
+                                                 const uint32_t (&g)[T], int32_t (&s)[T])
+{
+#pragma clang fp contract(off)
+    const int32_t K = A.K;
+    const uint64_t QB = A.beta_hdr[0];
+    const uint32_t Cb = (uint32_t)A.beta_hdr[1];
+    WordView wv[T];
+    int32_t z0[T], nds[T], nws[T], nks[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        doc[u].token(own[u], z0[u], nds[u]);
+        s[u] = z0[u];
+        wv[u] = load_word(A, w[u]);
+        nws[u] = nkw_lookup(A, wv[u], z0[u]);
+        nks[u] = A.nk[z0[u]];
+    }
+    for (int32_t j = 0; j < A.mh_steps; ++j) {
+        const bool word_step = (A.mode == 0) ? ((j & 1) == 0) : (A.mode == 1);
+        uint32_t x2[T];
+        int32_t t[T], ndt[T], nwt[T], nkt[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            uint32_t x[4];
+            philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+            x2[u] = x[2];
+            if (word_step) {
+                if (wv[u].kind & 2u) {
+                    const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                    const uint32_t rr = mulhi32(x[1], wv[u].C);
+                    const uint4 e = A.alias[wv[u].wk + bin];
+                    const bool keep = rr < e.x;
+                    t[u] = keep ? (int32_t)bin : (int32_t)e.y;
+                    nwt[u] = keep ? (int32_t)e.z : (int32_t)e.w;
+                } else {
+                    // pick the term by its integer mass, then draw from that term's table
+                    const double u3 = unit_open(x[3]);
+                    if (u3 * (double)(wv[u].QS + QB) < (double)wv[u].QS) {
+                        const uint32_t bin = mulhi32(x[0], wv[u].n);
+                        const uint32_t rr = mulhi32(x[1], wv[u].C);
+                        const uint4* __restrict__ e = A.ma + 2 * ((size_t)wv[u].list_off + bin);
+                        const uint4 e0 = e[0], e1 = e[1];
+                        const bool keep = rr < e0.x;
+                        t[u] = keep ? (int32_t)e0.y : (int32_t)e0.z;
+                        nwt[u] = keep ? (int32_t)e0.w : (int32_t)e1.x;
+                    } else {
+                        const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                        const uint32_t rr = mulhi32(x[1], Cb);
+                        const uint2 e = A.beta_alias[bin];
+                        t[u] = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
+                        nwt[u] = nkw_lookup(A, wv[u], t[u]);
+                    }
+                }
+                ndt[u] = doc[u].count(t[u]);
+            } else {
+                const double u0 = unit_open(x[0]);
+                const double Ld = (double)doc[u].L;
+                if (u0 * (Ld + A.alphabar) < Ld) {
+                    doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[u], ndt[u]);
+                } else {
+                    t[u] = (int32_t)mulhi32(x[1], (uint32_t)K);
+                    ndt[u] = doc[u].count(t[u]);
+                }
+                nwt[u] = nws[u];
+                if (t[u] != s[u]) nwt[u] = nkw_lookup(A, wv[u], t[u]);
+            }
+            nkt[u] = A.nk[t[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
+            const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
+            double num = (double)(ndt[u] - mt) + A.alpha;
+            num = num * ((double)(nwt[u] - mt) + A.beta);
+            num = num * ((double)(nks[u] - ms) + A.betabar);
+            double den = (double)(nds[u] - ms) + A.alpha;
+            den = den * ((double)(nws[u] - ms) + A.beta);
+            den = den * ((double)(nkt[u] - mt) + A.betabar);
+            if (word_step) {  // Eq. (8)
+                num = num * ((double)nws[u] + A.beta);
+                num = num * ((double)nkt[u] + A.betabar);
+                den = den * ((double)nwt[u] + A.beta);
+                den = den * ((double)nks[u] + A.betabar);
+            } else {          // Eq. (11)
+                num = num * ((double)nds[u] + A.alpha);
+                den = den * ((double)ndt[u] + A.alpha);
+            }
+            const double uu = unit_open(x2[u]);
+            const bool accept = (t[u] != s[u]) && (uu * den < num);
+            s[u] = accept ? t[u] : s[u];
+            nds[u] = accept ? ndt[u] : nds[u];
+            nws[u] = accept ? nwt[u] : nws[u];
+            nks[u] = accept ? nkt[u] : nks[u];
+        }
+    }
+}
+
 // T = tokens per thread; a tile has at most T * blockDim.x tokens.  MAXB bounds
 // the block size so that small blocks may use more registers per thread.
-template <int T, int MAXB>
+template <int T, int MAXB, bool HYBRID>
 __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
 {
     extern __shared__ int32_t smem[];
@@ -198,12 +341,16 @@ __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
         own[u] = (uint32_t)(i - b);
         w[u] = A.word[g[u]];
     }
-    mh_chains<T>(A, doc, own, w, g, s);
+    if constexpr (HYBRID)
+        mh_chains_hybrid<T>(A, doc, own, w, g, s);
+    else
+        mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
     for (int u = 0; u < T; ++u)
         if (live[u]) A.znew[g[u]] = s[u];
 }
 
+template <bool HYBRID>
 __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
 {
     constexpr int T = 2;
@@ -230,17 +377,20 @@ __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
             g[u] = (uint32_t)(tok0 + i);
             w[u] = A.word[g[u]];
         }
-        mh_chains<T>(A, doc, own, w, g, s);
+        if constexpr (HYBRID)
+            mh_chains_hybrid<T>(A, doc, own, w, g, s);
+        else
+            mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
         for (int u = 0; u < T; ++u)
             if (live[u]) A.znew[g[u]] = s[u];
     }
 }
 
-template <int T, int MAXB>
+template <int T, int MAXB, bool HYBRID>
 int launch_tiles_tb(lda_ctx* c, const SweepArgs& A, size_t lds)
 {
-    auto kern = sweep_tiles_kernel<T, MAXB>;
+    auto kern = sweep_tiles_kernel<T, MAXB, HYBRID>;
     if (lds > 48 * 1024)
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -249,12 +399,25 @@ int launch_tiles_tb(lda_ctx* c, const SweepArgs& A, size_t lds)
     return LDA_OK;
 }
 
-template <int T>
+template <int T, bool HYBRID>
 int launch_tiles_t(lda_ctx* c, const SweepArgs& A, size_t lds)
 {
-    if (c->sweep_block <= 256) return launch_tiles_tb<T, 256>(c, A, lds);
-    if (c->sweep_block <= 512) return launch_tiles_tb<T, 512>(c, A, lds);
-    return launch_tiles_tb<T, 1024>(c, A, lds);
+    if (c->sweep_block <= 256) return launch_tiles_tb<T, 256, HYBRID>(c, A, lds);
+    if (c->sweep_block <= 512) return launch_tiles_tb<T, 512, HYBRID>(c, A, lds);
+    return launch_tiles_tb<T, 1024, HYBRID>(c, A, lds);
+}
+
+template <bool HYBRID>
+int launch_tiles(lda_ctx* c, const SweepArgs& A, size_t lds)
+{
+    const int tpt = (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
+    if (tpt <= 1) return launch_tiles_t<1, HYBRID>(c, A, lds);
+    if (tpt <= 2) return launch_tiles_t<2, HYBRID>(c, A, lds);
+    if (tpt <= 4) return launch_tiles_t<4, HYBRID>(c, A, lds);
+    if (tpt <= 6) return launch_tiles_t<6, HYBRID>(c, A, lds);
+    if (tpt <= 8) return launch_tiles_t<8, HYBRID>(c, A, lds);
+    return fail(c, LDA_ERR_ARG, "sweep: more than 8 tokens per thread (tile %d, block %d)",
+                c->chunk_tokens, c->sweep_block);
 }
 
 // tokdoc[g] = index of token g's document inside its tile (0 for long documents)
@@ -287,32 +450,49 @@ int launch_tokdoc(lda_ctx* c)
     return LDA_OK;
 }
 
-int launch_sweep(lda_ctx* c, int32_t mh_steps)
+static SweepArgs make_sweep_args(lda_ctx* c, int32_t mh_steps)
 {
     SweepArgs A{};
     A.word = c->d_word; A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff;
-    A.chunk_doc = c->d_chunk_doc; A.tokdoc = c->d_tokdoc; A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias;
-    A.cap = c->d_cap; A.K = c->K; A.mh_steps = mh_steps; A.mode = c->opt.proposal_mode;
-    A.cap_tokens = c->chunk_tokens;
+    A.chunk_doc = c->d_chunk_doc; A.tokdoc = c->d_tokdoc; A.nkw = c->d_nkw; A.nk = c->d_nk;
+    A.alias = c->d_alias; A.cap = c->d_cap; A.K = c->K; A.mh_steps = mh_steps;
+    A.mode = c->opt.proposal_mode; A.cap_tokens = c->chunk_tokens;
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
     A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
+    A.metaA = c->d_metaA; A.metaB = c->d_metaB; A.ma = c->d_ma; A.hs = c->d_hs;
+    A.beta_alias = c->d_beta_alias; A.beta_hdr = c->d_beta_hdr;
     A.long_doc = c->d_long_doc; A.long_slot = c->d_long_slot;
     A.long_keys = c->d_long_keys; A.long_cnts = c->d_long_cnts;
+    return A;
+}
+
+int launch_sweep(lda_ctx* c, int32_t mh_steps)
+{
+    const SweepArgs A = make_sweep_args(c, mh_steps);
     const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
     if (c->n_chunks > 0) {
-        const int tpt = (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
-        int rc;
-        if (tpt <= 1) rc = launch_tiles_t<1>(c, A, lds);
-        else if (tpt <= 2) rc = launch_tiles_t<2>(c, A, lds);
-        else if (tpt <= 4) rc = launch_tiles_t<4>(c, A, lds);
-        else if (tpt <= 6) rc = launch_tiles_t<6>(c, A, lds);
-        else if (tpt <= 8) rc = launch_tiles_t<8>(c, A, lds);
-        else return fail(c, LDA_ERR_ARG, "sweep: more than 8 tokens per thread (tile %d, block %d)",
-                         c->chunk_tokens, c->sweep_block);
+        const int rc = launch_tiles<false>(c, A, lds);
         if (rc != LDA_OK) return rc;
     }
     if (c->n_long > 0) {
-        hipLaunchKernelGGL(sweep_long_docs_kernel, dim3(c->n_long), dim3(1024), 0, c->stream, A);
+        hipLaunchKernelGGL(sweep_long_docs_kernel<false>, dim3(c->n_long), dim3(1024), 0, c->stream,
+                           A);
+        LDA_HIP(c, hipGetLastError());
+    }
+    return LDA_OK;
+}
+
+int launch_sweep_hybrid(lda_ctx* c, int32_t mh_steps)
+{
+    const SweepArgs A = make_sweep_args(c, mh_steps);
+    const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
+    if (c->n_chunks > 0) {
+        const int rc = launch_tiles<true>(c, A, lds);
+        if (rc != LDA_OK) return rc;
+    }
+    if (c->n_long > 0) {
+        hipLaunchKernelGGL(sweep_long_docs_kernel<true>, dim3(c->n_long), dim3(1024), 0, c->stream,
+                           A);
         LDA_HIP(c, hipGetLastError());
     }
     return LDA_OK;

@@ -24,8 +24,8 @@ LDA_ERR_UNSUPPORTED = -5
 EXPORTS = [
     "lda_init", "lda_build_alias", "lda_sweep", "lda_rebuild_counts", "lda_loglik",
     "lda_num_tokens", "lda_sweep_index", "lda_get_z", "lda_set_z", "lda_get_nk",
-    "lda_get_nkw_row", "lda_get_ndk_row", "lda_get_alias_row", "lda_sync", "lda_last_error",
-    "lda_destroy",
+    "lda_get_nkw_row", "lda_get_ndk_row", "lda_get_alias_row", "lda_get_sparse_table",
+    "lda_get_beta_table", "lda_sync", "lda_last_error", "lda_destroy",
 ]
 
 
@@ -85,6 +85,11 @@ def load_library():
         "lda_get_nkw_row": (C.c_int, [vp, C.c_int32, _i32p]),
         "lda_get_ndk_row": (C.c_int, [vp, C.c_int64, _i32p]),
         "lda_get_alias_row": (C.c_int, [vp, C.c_int32, _u32p, _u32p, C.POINTER(C.c_uint32)]),
+        "lda_get_sparse_table": (C.c_int, [vp, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _i32p,
+                                           _u32p, _i32p, C.POINTER(C.c_uint32),
+                                           C.POINTER(C.c_uint64)]),
+        "lda_get_beta_table": (C.c_int, [vp, _u32p, _u32p, C.POINTER(C.c_uint32),
+                                         C.POINTER(C.c_uint64)]),
         "lda_sync": (C.c_int, [vp]),
         "lda_last_error": (C.c_char_p, [vp]),
         "lda_destroy": (None, [vp]),
@@ -191,3 +196,29 @@ class Lda:
         cap = C.c_uint32()
         self._ck(_lib.lda_get_alias_row(self._h, int(w), split, alias, C.byref(cap)))
         return split, alias, cap.value
+
+    def get_sparse_table(self, w):
+        """(topics, split, alias_topic, capacity, mass) of a mixture-form word."""
+        n = C.c_int32()
+        cap = C.c_uint32()
+        mass = C.c_uint64()
+        d = np.empty(1, np.int32)
+        u = np.empty(1, np.uint32)
+        self._ck(_lib.lda_get_sparse_table(self._h, int(w), 0, C.byref(n), d, u, d.copy(),
+                                           C.byref(cap), C.byref(mass)))
+        k = max(n.value, 1)
+        topics = np.empty(k, np.int32)
+        split = np.empty(k, np.uint32)
+        alias_topic = np.empty(k, np.int32)
+        self._ck(_lib.lda_get_sparse_table(self._h, int(w), k, C.byref(n), topics, split,
+                                           alias_topic, C.byref(cap), C.byref(mass)))
+        k = n.value
+        return topics[:k], split[:k], alias_topic[:k], cap.value, mass.value
+
+    def get_beta_table(self):
+        split = np.empty(self.K, np.uint32)
+        alias = np.empty(self.K, np.uint32)
+        cap = C.c_uint32()
+        mass = C.c_uint64()
+        self._ck(_lib.lda_get_beta_table(self._h, split, alias, C.byref(cap), C.byref(mass)))
+        return split, alias, cap.value, mass.value
