@@ -79,7 +79,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--mh-steps", type=int, default=2)
     ap.add_argument("--docs", type=int, default=0, help="use only the first DOCS documents' worth "
                     "of the workload (debugging; the result is then not the headline)")
@@ -109,11 +109,26 @@ def main():
     t_gen = time.perf_counter() - t0
     N = int(doff[-1])
 
+    # hybrid store (c4: dense rows for the head words; c5: no dense row): every word without a
+    # dense row draws from the mixture
+    hybrid = {}
+    store = "dense n_kw"
+    if args.workload in ("c4", "c5"):
+        dense_rows = cfg.dense_rows if args.workload == "c4" else -1
+        cnt = np.bincount(words, minlength=cfg.V)
+        tail = cnt[max(dense_rows, 0):]
+        hybrid = dict(dense_rows=dense_rows, dense_alias_min_count=int(tail.max()) + 1)
+        store = "hybrid n_kw (%s dense rows), mixture proposal below count %d" % (
+            max(dense_rows, 0), hybrid["dense_alias_min_count"])
+        del cnt, tail
+        args.no_cpu_baseline = True  # the oracle keeps a dense V x K table
+
     stream = torch.cuda.Stream()
     t0 = time.perf_counter()
     g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                 stream=stream.cuda_stream, sweep_chunk_tokens=args.chunk_tokens,
-                sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens)
+                sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens,
+                **hybrid)
     g.sync()
     t_init = time.perf_counter() - t0
 
@@ -179,8 +194,8 @@ def main():
         "data": "synthetic",
         "config": {
             "workload": "%s: D=%d docs, N=%d tokens, V=%d Zipf(%.2f), K=%d, alpha=%g, beta=%g, "
-                        "mh_steps=%d, dense n_kw" % (cfg.name, cfg.D, N, cfg.V, cfg.s, cfg.K,
-                                                     cfg.alpha, cfg.beta, args.mh_steps),
+                        "mh_steps=%d, %s" % (cfg.name, cfg.D, N, cfg.V, cfg.s, cfg.K,
+                                             cfg.alpha, cfg.beta, args.mh_steps, store),
             "sweep_tokens_per_s": N / (sweep_ms * 1e-3),
             "alias_ms": alias_ms, "sweep_ms": sweep_ms, "rebuild_ms": rebuild_ms,
             "wall_s_timed_region": wall, "corpus_gen_s": t_gen, "init_s": t_init,

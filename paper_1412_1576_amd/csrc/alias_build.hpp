@@ -15,8 +15,9 @@
 //
 // Src supplies q0(i); Sink receives (i, split, alias index) once per entry.  The
 // working lists live either in LDS or, for tables too large for it, in a global
-// workspace private to the workgroup (GLOBAL = true: accesses bypass the L1, and
-// barriers are preceded by a device-scope fence).
+// workspace private to the workgroup (GLOBAL = true: accesses bypass the L1; the
+// workgroup barrier orders them, no device-wide fence is needed or wanted -- on this
+// GPU a device-scope release writes back the whole L2).
 #pragma once
 
 #include "common.hpp"
@@ -137,7 +138,6 @@ struct ListMem {
     }
     __device__ __forceinline__ static void barrier()
     {
-        if constexpr (GLOBAL) __threadfence();
         __syncthreads();
     }
 };

@@ -73,10 +73,8 @@ __device__ __forceinline__ GlobalDocTable load_long_doc(int32_t* keys, int32_t* 
         __hip_atomic_store(&keys[i], kEmptyKey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&cnts[i], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __threadfence();
     __syncthreads();
     for (int32_t i = tid; i < L; i += nt) tab.insert(zdoc[i]);
-    __threadfence();
     __syncthreads();
     return tab;
 }

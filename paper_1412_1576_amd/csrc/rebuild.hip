@@ -168,7 +168,6 @@ __device__ __forceinline__ void fill_hash_row(uint2* __restrict__ hs, uint32_t l
 {
     const uint32_t cap = 1u << lg;
     for (uint32_t i = threadIdx.x; i < cap; i += blockDim.x) hs[i] = make_uint2(0xFFFFFFFFu, 0u);
-    __threadfence();
     __syncthreads();
     for (int32_t i = threadIdx.x; i < nnz; i += blockDim.x) {
         // the list was written by this workgroup a moment ago: read it past the L1
@@ -260,7 +259,6 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     }
     __syncthreads();
     for (int32_t r = tid; r < nnz; r += nt) sp_count[off + r] = head[r + 1] - head[r];
-    __threadfence();
     __syncthreads();
     const uint32_t hcap = hs_off[w + 1] - hs_off[w];
     fill_hash_row(hs + hs_off[w], log2_pow2(hcap), sp_topic + off, sp_count + off, nnz);
@@ -326,7 +324,6 @@ __global__ __launch_bounds__(1024) void scratch_compact_kernel(
     }
     const int32_t nnz = (int32_t)base;
     if (tid == 0) sp_nnz[w] = nnz;
-    __threadfence();
     __syncthreads();
     const uint32_t hcap = hs_off[w + 1] - hs_off[w];
     fill_hash_row(hs + hs_off[w], log2_pow2(hcap), sp_topic + off, sp_count + off, nnz);
