@@ -91,3 +91,67 @@ def test_c3_full_size_sampled(lda_mod, oracle_mod):
     """The benchmark's workload (K = 10,000), with the config's own 4 MH steps."""
     cfg = corpus.CONFIGS["c3"]
     sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10)
+
+
+def property_check(lda_mod, cfg, dense_rows, mh_steps, seed=5):
+    """Workloads whose dense V x K table the oracle cannot hold: invariants and numpy
+    recounts of the GPU's own assignment (the sweep's chains are covered by the oracle at
+    the same K on small vocabularies in test_gpu_hybrid.py)."""
+    rng = np.random.default_rng(seed)
+    doff, words = corpus.make_corpus(cfg)
+    N = int(doff[-1])
+    cnt = np.bincount(words, minlength=cfg.V)
+    min_count = int(cnt[max(dense_rows, 0):].max()) + 1
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                    dense_rows=dense_rows, dense_alias_min_count=min_count)
+    order = np.argsort(-cnt, kind="stable")
+    sample_words = list(order[:2]) + [int(order[len(order) // 3])] + \
+        list(rng.choice(cfg.V, 5, replace=False))
+    docs = rng.choice(cfg.D, 6, replace=False)
+    z_prev = g.get_z()
+    for it in range(2):
+        nk = g.get_nk()
+        assert np.array_equal(nk, np.bincount(z_prev, minlength=cfg.K)) and int(nk.sum()) == N
+        for w in sample_words:
+            row = np.bincount(z_prev[words == w], minlength=cfg.K)
+            assert np.array_equal(g.get_nkw_row(w), row), "n_kw row %d" % w
+        for d in docs:
+            row = np.bincount(z_prev[doff[d]:doff[d + 1]], minlength=cfg.K)
+            assert np.array_equal(g.get_ndk_row(d), row), "n_dk row %d" % d
+        if it == 1:
+            break
+        ll0 = g.loglik()[0]
+        g.build_alias()
+        # mixture tables: structural invariants of an alias table over the word's non-zeros
+        for w in sample_words:
+            if cnt[w] >= min_count:
+                continue
+            t, s, at, c, qs = g.get_sparse_table(w)
+            nz = np.flatnonzero(np.bincount(z_prev[words == w], minlength=cfg.K))
+            assert np.array_equal(t, nz)
+            if len(t):
+                assert s.min() >= 1 and s.max() <= c and np.isin(at, t).all()
+                mass = s.astype(np.int64).copy()
+                pos = np.searchsorted(t, at)
+                np.add.at(mass, pos[s < c], (c - s[s < c]).astype(np.int64))
+                assert mass.sum() == len(t) * c
+        g.sweep(mh_steps)
+        g.rebuild_counts()
+        z_new = g.get_z()
+        assert 0 <= z_new.min() and z_new.max() < cfg.K
+        assert (z_new != z_prev).mean() > 0.05
+        assert g.loglik()[0] > ll0  # one sweep from a uniform start improves the likelihood
+        z_prev = z_new
+    g.close()
+
+
+@pytest.mark.timeout(900)
+def test_c4_full_size_properties(lda_mod):
+    cfg = corpus.CONFIGS["c4"]
+    property_check(lda_mod, cfg, cfg.dense_rows, cfg.mh_steps)
+
+
+@pytest.mark.timeout(900)
+def test_c5_full_size_properties(lda_mod):
+    cfg = corpus.CONFIGS["c5"]
+    property_check(lda_mod, cfg, -1, cfg.mh_steps)
