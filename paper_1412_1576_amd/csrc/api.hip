@@ -57,7 +57,7 @@ void dev_free(T*& p)
 void free_all(lda_ctx* c)
 {
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
-    dev_free(c->d_gid); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
+    dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zw); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
     dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
@@ -355,6 +355,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_z, (size_t)N, "z"));
     TRY(dev_alloc(c, &c->d_znew, (size_t)N, "z (next)"));
     TRY(dev_alloc(c, &c->d_gid, (size_t)N, "word-major order"));
+    TRY(dev_alloc(c, &c->d_wpos, (size_t)N, "word-major positions"));
+    TRY(dev_alloc(c, &c->d_zw, (size_t)N, "word-major z"));
     TRY(dev_alloc(c, &c->d_woff, (size_t)V + 1, "word offsets"));
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
     TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));
@@ -426,6 +428,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY_HIP(hipStreamSynchronize(c->stream));
 #undef TRY
 #undef TRY_HIP
+    dev_free(c->d_gid);  // only wpos is needed from here on
     c->state = COUNTS_VALID;
     c->sweep_index = 0;
     *out = c;

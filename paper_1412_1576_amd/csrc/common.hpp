@@ -46,7 +46,9 @@ struct lda_ctx {
     int32_t* d_z = nullptr;     // [N] snapshot assignment
     int32_t* d_znew = nullptr;  // [N] next assignment
     // word-major view
-    int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order
+    int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order (init only)
+    int32_t* d_wpos = nullptr;  // [N] word-major position of token g (inverse of gid)
+    int32_t* d_zw = nullptr;    // [N] z in word-major order, refreshed by every count rebuild
     int32_t* d_woff = nullptr;  // [V+1] segment offsets
     // model
     int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)

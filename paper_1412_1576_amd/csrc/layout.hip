@@ -60,6 +60,15 @@ __global__ __launch_bounds__(256) void check_range_kernel(const int32_t* __restr
     if (any) atomicOr(bad, 1);
 }
 
+// wpos[gid[p]] = p
+__global__ __launch_bounds__(256) void invert_kernel(const int32_t* __restrict__ gid, int64_t n,
+                                                     int32_t* __restrict__ wpos)
+{
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n;
+         p += (int64_t)gridDim.x * blockDim.x)
+        wpos[gid[p]] = (int32_t)p;
+}
+
 unsigned grid_for(int64_t n, int block, unsigned cap = 8192)
 {
     int64_t b = (n + block - 1) / block;
@@ -119,6 +128,9 @@ int launch_layout(lda_ctx* c, const int32_t* /*h_word*/)
         return fail(c, e == hipErrorOutOfMemory ? LDA_ERR_OOM : LDA_ERR_HIP, "layout sort: %s",
                     hipGetErrorString(e));
 
+    hipLaunchKernelGGL(invert_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_gid, N,
+                       c->d_wpos);
+    LDA_HIP(c, hipGetLastError());
     hipLaunchKernelGGL(init_z_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_z, N,
                        c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
     LDA_HIP(c, hipGetLastError());

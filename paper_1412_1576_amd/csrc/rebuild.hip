@@ -1,9 +1,9 @@
 // Count rebuild (LightLDA Sec. 3: the sufficient statistics n_kw and n_k).
 //
 // n_kw: tokens are laid out word-major, so every word's tokens are one
-// contiguous segment; a workgroup histograms a tile of a segment in LDS
-// (gathering each token's new topic through the word-major -> CSR map) and
-// writes the dense row.  Words whose segment is longer than one tile are split
+// contiguous segment.  z is first scattered into that order (one random 4-byte
+// write per token, cheaper than a 128-byte line per gathered token); a workgroup
+// then histograms a tile of a segment in LDS and writes the dense row.  Words whose segment is longer than one tile are split
 // over several workgroups whose partial histograms are merged into a
 // pre-zeroed row with integer atomics (order-free, hence exact).
 // n_k: an LDS-privatised histogram of z over all tokens.
@@ -13,26 +13,61 @@ namespace lda {
 
 namespace {
 
+// zw[p] = topic of the p-th token in word-major order: zw[wpos[g]] = z[g].
+//
+// A word's tokens are ordered by document, so while g advances the writes into
+// one word's segment are sequential: a 128-byte line of zw is completed by 32
+// writes that are close in g.  Workgroups are dealt round-robin to the 8 XCDs,
+// each with its own L2; every XCD therefore takes one contiguous eighth of the
+// token range and walks it in order, so that the partially written lines of the
+// frequent words stay in that XCD's L2 until they are full instead of being
+// written back piecemeal by eight caches.
+constexpr int kXcds = 8;
+constexpr int kScatterPerThread = 4;
+
+__global__ __launch_bounds__(256) void scatter_wm_kernel(const int32_t* __restrict__ z,
+                                                         const int32_t* __restrict__ wpos,
+                                                         int64_t N, int32_t* __restrict__ zw)
+{
+    const int64_t per_xcd = (N + kXcds - 1) / kXcds;
+    const int xcd = blockIdx.x % kXcds;
+    const int64_t j = blockIdx.x / kXcds;
+    const int64_t lo = xcd * per_xcd;
+    const int64_t hi = (lo + per_xcd < N) ? lo + per_xcd : N;
+    const int64_t base = lo + j * (int64_t)(blockDim.x * kScatterPerThread);
+#pragma unroll
+    for (int u = 0; u < kScatterPerThread; ++u) {
+        const int64_t g = base + u * (int64_t)blockDim.x + threadIdx.x;
+        if (g < hi) zw[__builtin_nontemporal_load(&wpos[g])] = __builtin_nontemporal_load(&z[g]);
+    }
+}
+
+// blockIdx.x: tile; blockIdx.y: range of `span` topics (one range when the row fits LDS)
 __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __restrict__ tiles,
-                                                         const int32_t* __restrict__ gid,
-                                                         const int32_t* __restrict__ z,
-                                                         int32_t K, int32_t* __restrict__ nkw)
+                                                         const int32_t* __restrict__ zw,
+                                                         int32_t K, int32_t span,
+                                                         int32_t* __restrict__ nkw)
 {
     extern __shared__ int32_t hist[];
     const RebuildTile t = tiles[blockIdx.x];
+    const int32_t k0 = (int32_t)blockIdx.y * span;
+    const int32_t nk_r = ((k0 + span < K) ? k0 + span : K) - k0;
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < K; k += nt) hist[k] = 0;
+    for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
     __syncthreads();
-    for (int32_t p = t.p0 + tid; p < t.p1; p += nt) atomicAdd(&hist[z[gid[p]]], 1);
+    for (int32_t p = t.p0 + tid; p < t.p1; p += nt) {
+        const uint32_t r = (uint32_t)(zw[p] - k0);
+        if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
+    }
     __syncthreads();
-    int32_t* __restrict__ row = nkw + (size_t)t.w * (size_t)K;
+    int32_t* __restrict__ row = nkw + (size_t)t.w * (size_t)K + (size_t)k0;
     if (t.multi) {
-        for (int32_t k = tid; k < K; k += nt) {
+        for (int32_t k = tid; k < nk_r; k += nt) {
             const int32_t v = hist[k];
             if (v) atomicAdd(&row[k], v);
         }
     } else {
-        for (int32_t k = tid; k < K; k += nt) row[k] = hist[k];
+        for (int32_t k = tid; k < nk_r; k += nt) row[k] = hist[k];
     }
 }
 
@@ -75,30 +110,52 @@ __global__ __launch_bounds__(1024) void nk_hist_kernel(const int32_t* __restrict
 
 int max_rebuild_topics() { return 36 * 1024; }
 
-int launch_rebuild(lda_ctx* c)
+namespace {
+
+// word-major copy of z, then the dense rows by LDS histograms over topic ranges
+int launch_dense_rows(lda_ctx* c)
 {
     const int32_t K = c->K;
-    if (K > max_rebuild_topics())
-        return fail(c, LDA_ERR_UNSUPPORTED, "count rebuild supports K <= %d", max_rebuild_topics());
-    const size_t lds = sizeof(int32_t) * (size_t)K;
-    if (lds > 48 * 1024) {
+    {
+        const int64_t per_xcd = (c->N + kXcds - 1) / kXcds;
+        const int64_t per_block = 256 * kScatterPerThread;
+        const int64_t blocks = ((per_xcd + per_block - 1) / per_block) * kXcds;
+        hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(256), 0, c->stream,
+                           c->d_z, c->d_wpos, c->N, c->d_zw);
+    }
+    LDA_HIP(c, hipGetLastError());
+    if (c->n_tiles == 0) return LDA_OK;
+    const int32_t nr = (K + max_rebuild_topics() - 1) / max_rebuild_topics();
+    const int32_t span = (((K + nr - 1) / nr) + 63) / 64 * 64;
+    const size_t lds = sizeof(int32_t) * (size_t)span;
+    if (lds > 48 * 1024)
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nkw_tiles_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    }
     if (c->n_multi_words > 0) {
         hipLaunchKernelGGL(zero_rows_kernel, dim3(c->n_multi_words), dim3(256), 0, c->stream,
                            c->d_multi_words, K, c->d_nkw);
         LDA_HIP(c, hipGetLastError());
     }
-    // block size: small rows do not need 1024 threads
-    int block = 1024;
-    if (K <= 512) block = 256;
-    hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles), dim3(block), lds, c->stream, c->d_tiles,
-                       c->d_gid, c->d_z, K, c->d_nkw);
+    hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
+                       dim3(span <= 512 ? 256 : 1024), lds, c->stream, c->d_tiles, c->d_zw, K, span,
+                       c->d_nkw);
     LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
 
+}  // namespace
+
+int launch_rebuild(lda_ctx* c)
+{
+    const int32_t K = c->K;
+    if (K > max_rebuild_topics())
+        return fail(c, LDA_ERR_UNSUPPORTED, "count rebuild supports K <= %d", max_rebuild_topics());
+    int rc = launch_dense_rows(c);
+    if (rc != LDA_OK) return rc;
+    const size_t lds = sizeof(int32_t) * (size_t)K;
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(fill_i32_kernel, dim3(64), dim3(256), 0, c->stream, c->d_nk, (int64_t)K, 0);
     LDA_HIP(c, hipGetLastError());
     int64_t blocks = (c->N + 65535) / 65536;
@@ -109,6 +166,8 @@ int launch_rebuild(lda_ctx* c)
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }
+
+int launch_dense_rows_hybrid(lda_ctx* c) { return launch_dense_rows(c); }
 
 }  // namespace lda
 
@@ -122,19 +181,6 @@ namespace lda {
 namespace {
 
 constexpr int32_t kSortPad = 0x7FFFFFFF;
-
-// n_kw of the dense head rows by atomics (rows too long for an LDS histogram)
-__global__ __launch_bounds__(256) void nkw_atomic_kernel(const int32_t* __restrict__ word,
-                                                         const int32_t* __restrict__ z, int64_t N,
-                                                         int32_t H, int32_t K,
-                                                         int32_t* __restrict__ nkw)
-{
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < N;
-         g += (int64_t)gridDim.x * blockDim.x) {
-        const int32_t w = word[g];
-        if (w < H) atomicAdd(&nkw[(size_t)w * (size_t)K + (size_t)z[g]], 1);
-    }
-}
 
 // n_k for K beyond one LDS histogram: blockIdx.y selects a range of `span` topics
 __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __restrict__ z,
@@ -192,7 +238,7 @@ __device__ __forceinline__ uint32_t log2_pow2(uint32_t x) { return 31u - (uint32
 // fill the hash row.
 __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     const int32_t* __restrict__ words, int32_t P, const int32_t* __restrict__ woff,
-    const int32_t* __restrict__ gid, const int32_t* __restrict__ z,
+    const int32_t* __restrict__ zw,
     const uint32_t* __restrict__ sp_off, int32_t* __restrict__ sp_topic,
     int32_t* __restrict__ sp_count, int32_t* __restrict__ sp_nnz,
     const uint32_t* __restrict__ hs_off, uint2* __restrict__ hs)
@@ -211,7 +257,7 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     }
     int32_t Q = 2;  // sort size: smallest power of two >= c
     while (Q < c) Q <<= 1;
-    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? z[gid[p0 + i]] : kSortPad;
+    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? zw[p0 + i] : kSortPad;
     __syncthreads();
     for (int32_t k = 2; k <= Q; k <<= 1) {
         for (int32_t j = k >> 1; j > 0; j >>= 1) {
@@ -268,8 +314,7 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
 __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __restrict__ words,
                                                            int32_t n_words, int32_t tile,
                                                            const int32_t* __restrict__ woff,
-                                                           const int32_t* __restrict__ gid,
-                                                           const int32_t* __restrict__ z, int32_t K,
+                                                           const int32_t* __restrict__ zw, int32_t K,
                                                            int32_t* __restrict__ scratch)
 {
     const int32_t wi = blockIdx.y;
@@ -280,7 +325,7 @@ __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __rest
     for (int32_t b = p0 + (int32_t)blockIdx.x * tile; b < p1; b += (int32_t)gridDim.x * tile) {
         const int32_t e = (b + tile < p1) ? b + tile : p1;
         for (int32_t p = b + (int32_t)threadIdx.x; p < e; p += (int32_t)blockDim.x)
-            atomicAdd(&row[z[gid[p]]], 1);
+            atomicAdd(&row[zw[p]], 1);
     }
 }
 
@@ -334,31 +379,10 @@ __global__ __launch_bounds__(1024) void scratch_compact_kernel(
 int launch_rebuild_hybrid(lda_ctx* c)
 {
     const int32_t K = c->K;
-    // ---- dense head rows ----
-    if (c->H > 0) {
-        if (K <= max_rebuild_topics()) {
-            const size_t lds = sizeof(int32_t) * (size_t)K;
-            if (lds > 48 * 1024)
-                LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nkw_tiles_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            if (c->n_multi_words > 0) {
-                hipLaunchKernelGGL(zero_rows_kernel, dim3(c->n_multi_words), dim3(256), 0, c->stream,
-                                   c->d_multi_words, K, c->d_nkw);
-                LDA_HIP(c, hipGetLastError());
-            }
-            if (c->n_tiles > 0) {
-                hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles), dim3(K <= 512 ? 256 : 1024),
-                                   lds, c->stream, c->d_tiles, c->d_gid, c->d_z, K, c->d_nkw);
-                LDA_HIP(c, hipGetLastError());
-            }
-        } else {
-            hipLaunchKernelGGL(fill_i32_kernel, dim3(4096), dim3(256), 0, c->stream, c->d_nkw,
-                               (int64_t)c->H * (int64_t)K, 0);
-            LDA_HIP(c, hipGetLastError());
-            hipLaunchKernelGGL(nkw_atomic_kernel, dim3(8192), dim3(256), 0, c->stream, c->d_word,
-                               c->d_z, c->N, c->H, K, c->d_nkw);
-            LDA_HIP(c, hipGetLastError());
-        }
+    // ---- word-major copy of z and the dense head rows ----
+    {
+        const int rc = launch_dense_rows_hybrid(c);
+        if (rc != LDA_OK) return rc;
     }
     // ---- sparse rows: LDS sort classes ----
     static const int32_t kSortCap[4] = {64, 512, 4096, 16384};
@@ -371,7 +395,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         const int threads = P <= 64 ? 64 : (P <= 512 ? 256 : 1024);
         hipLaunchKernelGGL(sparse_rows_sort_kernel, dim3(c->n_sortsp_class[cl]), dim3(threads), lds,
-                           c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_gid, c->d_z,
+                           c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_zw,
                            c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz, c->d_hs_off,
                            c->d_hs);
         LDA_HIP(c, hipGetLastError());
@@ -380,7 +404,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
     for (int32_t b0 = 0; b0 < c->n_bigsp; b0 += c->n_scratch_rows) {
         const int32_t nb = std::min(c->n_scratch_rows, c->n_bigsp - b0);
         hipLaunchKernelGGL(scratch_hist_kernel, dim3(64, nb), dim3(256), 0, c->stream,
-                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_gid, c->d_z, K,
+                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zw, K,
                            c->d_scratch_rows);
         LDA_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(scratch_compact_kernel, dim3(nb), dim3(1024), 0, c->stream,
