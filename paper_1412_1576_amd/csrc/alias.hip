@@ -34,9 +34,15 @@ struct DenseSrc {
 struct DenseSink {
     uint4* __restrict__ out;
     const int32_t* __restrict__ row;
-    __device__ __forceinline__ void put(int32_t k, uint32_t split, uint32_t al) const
+    struct Loaded { int32_t own, other; };
+    __device__ __forceinline__ Loaded load(int32_t k, uint32_t al) const
     {
-        out[k] = make_uint4(split, al, (uint32_t)row[k], (uint32_t)row[al]);
+        return Loaded{row[k], row[al]};
+    }
+    __device__ __forceinline__ void store(int32_t k, uint32_t split, uint32_t al,
+                                          const Loaded& v) const
+    {
+        out[k] = make_uint4(split, al, (uint32_t)v.own, (uint32_t)v.other);
     }
 };
 
@@ -58,11 +64,17 @@ struct SparseSink {
     uint4* __restrict__ out;
     const int32_t* __restrict__ topic;
     const int32_t* __restrict__ count;
-    __device__ __forceinline__ void put(int32_t i, uint32_t split, uint32_t al) const
+    struct Loaded { int32_t t_own, t_other, n_own, n_other; };
+    __device__ __forceinline__ Loaded load(int32_t i, uint32_t al) const
+    {
+        return Loaded{topic[i], topic[al], count[i], count[al]};
+    }
+    __device__ __forceinline__ void store(int32_t i, uint32_t split, uint32_t,
+                                          const Loaded& v) const
     {
         out[2 * (size_t)i] =
-            make_uint4(split, (uint32_t)topic[i], (uint32_t)topic[al], (uint32_t)count[i]);
-        out[2 * (size_t)i + 1] = make_uint4((uint32_t)count[al], 0u, 0u, 0u);
+            make_uint4(split, (uint32_t)v.t_own, (uint32_t)v.t_other, (uint32_t)v.n_own);
+        out[2 * (size_t)i + 1] = make_uint4((uint32_t)v.n_other, 0u, 0u, 0u);
     }
 };
 
@@ -79,7 +91,10 @@ struct BetaSrc {
 
 struct BetaSink {
     uint2* __restrict__ out;
-    __device__ __forceinline__ void put(int32_t k, uint32_t split, uint32_t al) const
+    struct Loaded {};
+    __device__ __forceinline__ Loaded load(int32_t, uint32_t) const { return Loaded{}; }
+    __device__ __forceinline__ void store(int32_t k, uint32_t split, uint32_t al,
+                                          const Loaded&) const
     {
         out[k] = make_uint2(split, al);
     }

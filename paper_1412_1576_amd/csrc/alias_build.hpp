@@ -13,7 +13,8 @@
 //             alias = next heavy if split < C, else itself
 // so the build is prefix sums over the two lists and bounded searches.
 //
-// Src supplies q0(i); Sink receives (i, split, alias index) once per entry.  The
+// Src supplies q0(i); Sink gathers what entry i's output needs (load) and writes the
+// entry (store), once per entry.  The
 // working lists live either in LDS or, for tables too large for it, in a global
 // workspace private to the workgroup (GLOBAL = true: accesses bypass the L1; the
 // workgroup barrier orders them, no device-wide fence is needed or wanted -- on this
@@ -280,6 +281,9 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
     b_run = b_wave;
     uint32_t b_prev = 0;  // partner of the last light met so far
     uint32_t a_prev = 0;  // partner of the last heavy met so far
+    typename Sink::Loaded pend_v{};
+    int32_t pend_k = -1;
+    uint32_t pend_split = 0, pend_al = 0;
     for (int32_t k0 = kb; k0 < ke; k0 += kWave) {
         const int32_t k = k0 + lane;
         const bool valid = k < ke;
@@ -326,7 +330,16 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
             split = (uint32_t)sp;
             al = (sp < C) ? M::ld(&hidx[b_own + 1]) : (uint32_t)k;
         }
-        if (valid) sink.put(k, split, al);
+        // An entry's output needs values gathered from global memory (the counts of its
+        // two outcomes); the gathers are issued now and the entry is stored one round
+        // later, so their latency overlaps the next round's searches.
+        typename Sink::Loaded cur_v{};
+        if (valid) cur_v = sink.load(k, al);
+        if (pend_k >= 0) sink.store(pend_k, pend_split, pend_al, pend_v);
+        pend_k = valid ? k : -1;
+        pend_split = split;
+        pend_al = al;
+        pend_v = cur_v;
         b_prev = b_hi;
         a_prev = a_hi;
         const uint32_t nl = (uint32_t)__popcll(lmask);
@@ -334,6 +347,7 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
         a_run += nl;
         b_run += nv - nl;
     }
+    if (pend_k >= 0) sink.store(pend_k, pend_split, pend_al, pend_v);
     Q0_out = Q0;
     C_out = (uint32_t)C;
 }
