@@ -23,9 +23,10 @@ namespace {
 // frequent words stay in that XCD's L2 until they are full instead of being
 // written back piecemeal by eight caches.
 constexpr int kXcds = 8;
-constexpr int kScatterPerThread = 4;
+constexpr int kScatterPerThread = 1;
+constexpr int kScatterBlock = 1024;
 
-__global__ __launch_bounds__(256) void scatter_wm_kernel(const int32_t* __restrict__ z,
+__global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restrict__ z,
                                                          const int32_t* __restrict__ wpos,
                                                          int64_t N, int32_t* __restrict__ zw)
 {
@@ -118,9 +119,9 @@ int launch_dense_rows(lda_ctx* c)
     const int32_t K = c->K;
     {
         const int64_t per_xcd = (c->N + kXcds - 1) / kXcds;
-        const int64_t per_block = 256 * kScatterPerThread;
+        const int64_t per_block = kScatterBlock * kScatterPerThread;
         const int64_t blocks = ((per_xcd + per_block - 1) / per_block) * kXcds;
-        hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(256), 0, c->stream,
+        hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(kScatterBlock), 0, c->stream,
                            c->d_z, c->d_wpos, c->N, c->d_zw);
     }
     LDA_HIP(c, hipGetLastError());
