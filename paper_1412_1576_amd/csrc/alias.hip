@@ -109,7 +109,7 @@ struct DenseArgs {
     double beta, betabar;
     uint4* alias;
     uint32_t* cap;   // nullable
-    uint4* metaA;    // nullable
+    uint4* metaA;    // nullable; word w at [2w]
     int32_t use_cache;
     unsigned char* ws;  // GLOBAL: list memory, ws_stride bytes per workgroup
     size_t ws_stride;
@@ -127,7 +127,7 @@ __device__ __forceinline__ void dense_table(const DenseArgs& a, int32_t w, unsig
     build_alias_table<GLOBAL>(K, src, sink, lists, a.use_cache != 0, Q0, C);
     if (threadIdx.x == 0) {
         if (a.cap) a.cap[w] = C;
-        if (a.metaA) a.metaA[w] = make_uint4((uint32_t)K, C, 0u, 0u);
+        if (a.metaA) a.metaA[2 * (size_t)w] = make_uint4((uint32_t)K, C, 0u, 0u);
     }
 }
 
@@ -171,7 +171,7 @@ __device__ __forceinline__ void mix_table(const MixArgs& a, int32_t w, unsigned 
 {
     const int32_t n = a.sp_nnz[w];
     if (n <= 0) {  // a word without tokens is never drawn from
-        if (threadIdx.x == 0) a.metaA[w] = make_uint4(0u, 0u, 0u, 0u);
+        if (threadIdx.x == 0) a.metaA[2 * (size_t)w] = make_uint4(0u, 0u, 0u, 0u);
         return;
     }
     const size_t off = a.sp_off[w];
@@ -181,7 +181,7 @@ __device__ __forceinline__ void mix_table(const MixArgs& a, int32_t w, unsigned 
     uint32_t C;
     build_alias_table<GLOBAL>(n, src, sink, lists, a.use_cache != 0, QS, C);
     if (threadIdx.x == 0)
-        a.metaA[w] = make_uint4((uint32_t)n, C, (uint32_t)QS, (uint32_t)(QS >> 32));
+        a.metaA[2 * (size_t)w] = make_uint4((uint32_t)n, C, (uint32_t)QS, (uint32_t)(QS >> 32));
 }
 
 __global__ __launch_bounds__(256) void alias_mix_lds_kernel(MixArgs a)

@@ -67,7 +67,7 @@ void free_all(lda_ctx* c)
     for (int i = 0; i < 4; ++i) dev_free(c->d_sortsp_class[i]);
     dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
     dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
-    dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); dev_free(c->d_metaB);
+    dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); c->d_metaB = nullptr;
     dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
     dev_free(c->d_big_list); dev_free(c->d_scratch_rows); dev_free(c->d_bigsp_words);
 }
@@ -95,7 +95,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->h_sp_off.assign((size_t)V + 1, 0);
     c->h_hs_off.assign((size_t)V + 1, 0);
     std::vector<int32_t> dense_alias, mix, sparse, compact, bigsp, mixc[5], sortc[4];
-    std::vector<uint4> metaB(V);
+    std::vector<uint4> meta(2 * (size_t)V, make_uint4(0u, 0u, 0u, 0u));
     static const int32_t mix_cap[4] = {64, 512, 4096, 0};
     static const int32_t sort_cap[4] = {64, 512, 4096, 16384};
     const int32_t lds_max = max_lds_table_entries();
@@ -143,7 +143,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
                 }
             }
         }
-        metaB[w] = make_uint4(c->h_sp_off[w], c->h_hs_off[w], lg, kind);
+        meta[2 * (size_t)w + 1] = make_uint4(c->h_sp_off[w], c->h_hs_off[w], lg, kind);
         if (list_total > 0x7FFFFFFFull || hash_total > 0xFFFFFFFFull)
             return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: sparse rows exceed 2^31 entries");
     }
@@ -177,10 +177,10 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     }
     UP(d_sp_off, c->h_sp_off, "list offsets");
     UP(d_hs_off, c->h_hs_off, "hash offsets");
-    UP(d_metaB, metaB, "word descriptors");
+    UP(d_metaA, meta, "word descriptors");
+    c->d_metaB = c->d_metaA + 1;
 #undef UP
 #define AL(field, count, what) do { rc = dev_alloc(c, &c->field, (size_t)(count), what); if (rc != LDA_OK) return rc; } while (0)
-    AL(d_metaA, V, "word tables");
     AL(d_sp_topic, list_total, "sparse rows");
     AL(d_sp_count, list_total, "sparse rows");
     AL(d_sp_nnz, V, "sparse rows");
@@ -188,7 +188,6 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     AL(d_ma, 2 * list_total, "mixture tables");
     AL(d_beta_alias, K, "beta table");
     AL(d_beta_hdr, 2, "beta table");
-    LDA_HIP(c, hipMemsetAsync(c->d_metaA, 0, sizeof(uint4) * (size_t)V, c->stream));
     LDA_HIP(c, hipMemsetAsync(c->d_sp_nnz, 0, sizeof(int32_t) * (size_t)V, c->stream));
     // global list memory for tables too large for LDS
     const bool need_big = (K > lds_max && (c->n_dense_alias > 0 || c->n_mix > 0)) ||
@@ -201,7 +200,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     }
     if (c->n_bigsp > 0) {
         int64_t rows = (int64_t)(1.0e9 / (4.0 * (double)K));
-        c->n_scratch_rows = (int32_t)std::max<int64_t>(1, std::min<int64_t>(64, rows));
+        c->n_scratch_rows = (int32_t)std::max<int64_t>(1, std::min<int64_t>(256, rows));
         AL(d_scratch_rows, (size_t)c->n_scratch_rows * (size_t)K, "scratch rows");
         LDA_HIP(c, hipMemsetAsync(c->d_scratch_rows, 0,
                                   sizeof(int32_t) * (size_t)c->n_scratch_rows * (size_t)K, c->stream));
@@ -587,7 +586,7 @@ int lda_get_alias_row(lda_ctx* c, int32_t w, uint32_t* split, uint32_t* alias, u
                               sizeof(uint4) * (size_t)c->K, hipMemcpyDeviceToHost, c->stream));
     if (c->hybrid) {
         uint4 m;
-        LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
+        LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + 2 * (size_t)w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
         LDA_HIP(c, hipStreamSynchronize(c->stream));
         *cap = m.y;
     } else {
@@ -612,7 +611,7 @@ int lda_get_sparse_table(lda_ctx* c, int32_t w, int32_t cap_entries, int32_t* n,
     if (!c->hybrid || (c->h_wkind[w] & 2))
         return fail(c, LDA_ERR_ARG, "lda_get_sparse_table: word %d draws from a dense table", w);
     uint4 m;
-    LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
+    LDA_HIP(c, hipMemcpyAsync(&m, c->d_metaA + 2 * (size_t)w, sizeof(uint4), hipMemcpyDeviceToHost, c->stream));
     LDA_HIP(c, hipStreamSynchronize(c->stream));
     *n = (int32_t)m.x;
     if (cap) *cap = m.y;

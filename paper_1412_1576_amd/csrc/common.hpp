@@ -95,8 +95,10 @@ struct lda_ctx {
     uint32_t* d_hs_off = nullptr;        // [V+1] first hash slot of word w (power-of-two capacity)
     uint2* d_hs = nullptr;               // (topic, count) slots, topic = -1: empty
     uint4* d_ma = nullptr;               // mixture tables: two uint4 per list entry
-    uint4* d_metaA = nullptr;            // [V] (entries n, capacity C, QS low, QS high)
-    uint4* d_metaB = nullptr;            // [V] (list offset, hash offset, hash mask, kind)
+    // one 32-byte record per word, [2w] = (entries n, capacity C, QS low, QS high) rewritten by
+    // every table build, [2w+1] = (list offset, hash offset, log2 hash slots, kind) fixed
+    uint4* d_metaA = nullptr;            // [2V]
+    uint4* d_metaB = nullptr;            // = d_metaA + 1 (not owned)
     uint2* d_beta_alias = nullptr;       // [K] shared table of the beta term (split, alias)
     uint64_t* d_beta_hdr = nullptr;      // [2] QB, capacity
     unsigned char* d_big_ws = nullptr;   // list memory of the workgroups that build big tables

@@ -208,6 +208,16 @@ __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __r
     }
 }
 
+// n_k for very large K: one global atomic per token (more topic ranges than this is
+// worth would each re-read all of z)
+__global__ __launch_bounds__(256) void nk_atomic_kernel(const int32_t* __restrict__ z, int64_t N,
+                                                        int32_t* __restrict__ nk)
+{
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < N;
+         g += (int64_t)gridDim.x * blockDim.x)
+        atomicAdd(&nk[z[g]], 1);
+}
+
 // hash row of word w from its list: clear, then insert every (topic, count)
 __device__ __forceinline__ void fill_hash_row(uint2* __restrict__ hs, uint32_t lg,
                                               const int32_t* __restrict__ topic,
@@ -427,6 +437,9 @@ int launch_rebuild_hybrid(lda_ctx* c)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(nk_hist_kernel, dim3((unsigned)blocks), dim3(1024), lds, c->stream,
                            c->d_z, c->N, K, c->d_nk);
+    } else if (K > 8 * span) {
+        hipLaunchKernelGGL(nk_atomic_kernel, dim3(8192), dim3(256), 0, c->stream, c->d_z, c->N,
+                           c->d_nk);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)span;
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_ranges_kernel),

@@ -31,8 +31,8 @@ struct SweepArgs {
     double alpha, beta, alphabar, betabar;
     uint32_t seed_lo, seed_hi, sweep;
     // hybrid store / mixture proposal (null in the all-dense mode)
-    const uint4* metaA;       // (entries n, capacity C, QS low, QS high) per word
-    const uint4* metaB;       // (list offset, hash offset, log2 hash slots, kind) per word
+    const uint4* metaA;       // word w at [2w]: (entries n, capacity C, QS low, QS high)
+    const uint4* metaB;       // = metaA + 1, word w at [2w]: (list offset, hash offset, log2 slots, kind)
     const uint4* ma;          // mixture bins, two uint4 per list entry
     const uint2* hs;          // hash rows (topic, count)
     const uint2* beta_alias;  // shared beta-term table
@@ -185,7 +185,7 @@ struct WordView {
 
 __device__ __forceinline__ WordView load_word(const SweepArgs& A, int32_t w)
 {
-    const uint4 a = A.metaA[w], b = A.metaB[w];
+    const uint4 a = A.metaA[2 * (size_t)w], b = A.metaB[2 * (size_t)w];  // one 32-byte record
     WordView v;
     v.n = a.x; v.C = a.y; v.QS = ((uint64_t)a.w << 32) | a.z;
     v.list_off = b.x; v.hs_off = b.y; v.lg = b.z; v.kind = b.w;
