@@ -74,7 +74,8 @@ typedef struct lda_options {
 /*
  * lda_init -- take a corpus and set up the sampler state (problem statement: Sec. 3).
  *   D            number of documents (>= 1); empty documents are legal
- *   V, K         vocabulary size and number of topics (>= 1)
+ *   V, K         vocabulary size and number of topics (>= 1); K <= 2^20 - 2, and K <= 12288
+ *                unless the hybrid store is selected (LDA_ERR_UNSUPPORTED otherwise)
  *   doc_offsets  [D+1] host, doc_offsets[0] = 0, non-decreasing, N = doc_offsets[D] in [1, 2^31-2]
  *   word_ids     [N] host, each in [0, V)
  *   alpha, beta  symmetric Dirichlet parameters (> 0) of Eq. (1)
@@ -90,8 +91,11 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
 
 /*
  * lda_build_alias -- word-proposal tables of Eq. (6) for every word, from the
- * current counts: per topic bin a split point and an alias (Sec. 4.2, Fig. 2),
- * plus the bin capacity of the word.  COUNTS_VALID -> ALIAS_VALID.
+ * current counts: per bin a split point and an alias (Sec. 4.2, Fig. 2), plus the
+ * bin capacity of the table.  Words of the dense form get one table over all K
+ * topics; words of the mixture form (Sec. 4.2, the sparsified table) one table
+ * over their non-zero topics, and all of them share one table over
+ * beta/(n_k + V beta).  COUNTS_VALID -> ALIAS_VALID.
  */
 int lda_build_alias(lda_ctx* ctx);
 
@@ -106,9 +110,10 @@ int lda_sweep(lda_ctx* ctx, int32_t mh_steps);
 
 /*
  * lda_rebuild_counts -- recount n_kw (per-word histogram of the word-major
- * token segments) and n_k from the current assignment; the per-document counts
- * n_kd are formed inside the sweep from the document's assignments.
- * SWEPT (or any state) -> COUNTS_VALID.
+ * token segments: dense rows, and for words without a dense row the sorted
+ * (topic, count) list and hash row of Sec. 5) and n_k from the current
+ * assignment; the per-document counts n_kd are formed inside the sweep from the
+ * document's assignments.  SWEPT (or any state) -> COUNTS_VALID.
  */
 int lda_rebuild_counts(lda_ctx* ctx);
 
