@@ -117,7 +117,9 @@ def main():
         dense_rows = cfg.dense_rows if args.workload == "c4" else -1
         cnt = np.bincount(words, minlength=cfg.V)
         tail = cnt[max(dense_rows, 0):]
-        hybrid = dict(dense_rows=dense_rows, dense_alias_min_count=int(tail.max()) + 1)
+        # dense K-bin tables only for words with at least K tokens (rows that can be dense)
+        hybrid = dict(dense_rows=dense_rows,
+                      dense_alias_min_count=max(int(tail.max()) + 1, cfg.K))
         store = "hybrid n_kw (%s dense rows), mixture proposal below count %d" % (
             max(dense_rows, 0), hybrid["dense_alias_min_count"])
         del cnt, tail

@@ -101,7 +101,8 @@ def property_check(lda_mod, cfg, dense_rows, mh_steps, seed=5):
     doff, words = corpus.make_corpus(cfg)
     N = int(doff[-1])
     cnt = np.bincount(words, minlength=cfg.V)
-    min_count = int(cnt[max(dense_rows, 0):].max()) + 1
+    # as bench.py: dense tables only for words with at least K tokens and a dense row
+    min_count = max(int(cnt[max(dense_rows, 0):].max()) + 1, cfg.K)
     g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                     dense_rows=dense_rows, dense_alias_min_count=min_count)
     order = np.argsort(-cnt, kind="stable")

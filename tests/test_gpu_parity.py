@@ -200,3 +200,27 @@ def test_state_machine_and_checkpoint(lda_mod, oracle_mod):
         lda_mod.Lda(doff, w2, cfg.V, cfg.K, cfg.alpha, cfg.beta)
     assert e.value.code == lda_mod.LDA_ERR_ARG
     g.close(); h.close()
+
+
+def test_proposal_ablation_qualitative(lda_mod):
+    """The paper's ablation (Sec. 7, cycle vs doc-only vs word-only proposals): with few MH
+    steps the word-proposal alone sparsifies the word-topic table (best word-likelihood, worst
+    doc-likelihood), the doc-proposal alone the doc-topic table (the reverse), and the cycle of
+    the two lies between them on both parts.  Planted-topic corpus, 40 sweeps of 2 steps.
+    (The paper's further claim that the cycle reaches the best total is not reproduced on
+    this small corpus: word-only ends slightly higher.)"""
+    cfg = corpus.CONFIGS["c1"]
+    doff, words = corpus.make_corpus(cfg)
+    res = {}
+    for mode in (0, 1, 2):
+        g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=1, proposal_mode=mode)
+        first = g.loglik()[0]
+        for it in range(40):
+            g.build_alias(); g.sweep(2); g.rebuild_counts()
+        res[mode] = g.loglik()
+        assert res[mode][0] > first + 1e5
+        g.close()
+    (tot_c, doc_c, word_c), (tot_w, doc_w, word_w), (tot_d, doc_d, word_d) = res[0], res[1], res[2]
+    assert word_w > word_c > word_d
+    assert doc_d > doc_c > doc_w
+    assert tot_c > tot_d
