@@ -38,11 +38,9 @@ _u32p = np.ctypeslib.ndpointer(np.uint32, flags="C_CONTIGUOUS")
 _u64p = np.ctypeslib.ndpointer(np.uint64, flags="C_CONTIGUOUS")
 
 
-def lib():
-    global _lib
-    if _lib is not None:
-        return _lib
-    L = C.CDLL(build_oracle())
+def bind(path):
+    """Load an oracle shared library and declare its signatures."""
+    L = C.CDLL(path)
     vp = C.c_void_p
     sig = {
         "ldaref_philox4x32_10": (None, [_u32p, _u32p, _u32p]),
@@ -80,8 +78,14 @@ def lib():
         f = getattr(L, name)
         f.restype = res
         f.argtypes = args
-    _lib = L
     return L
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = bind(build_oracle())
+    return _lib
 
 
 class OracleError(RuntimeError):

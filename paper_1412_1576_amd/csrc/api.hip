@@ -11,8 +11,6 @@ namespace lda {
 
 static thread_local std::string g_init_error;
 
-void set_init_error(const char* msg) { g_init_error = msg; }
-
 int fail(lda_ctx* c, int code, const char* fmt, ...)
 {
     char buf[512];
@@ -62,14 +60,14 @@ void free_all(lda_ctx* c)
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
     dev_free(c->d_flag);
-    dev_free(c->d_wkind); dev_free(c->d_dense_alias_words); dev_free(c->d_mix_words);
+    dev_free(c->d_dense_alias_words);
     for (int i = 0; i < 5; ++i) dev_free(c->d_mix_class[i]);
     for (int i = 0; i < 4; ++i) dev_free(c->d_sortsp_class[i]);
     dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
     dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
     dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); c->d_metaB = nullptr;
     dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
-    dev_free(c->d_big_list); dev_free(c->d_scratch_rows); dev_free(c->d_bigsp_words);
+    dev_free(c->d_scratch_rows); dev_free(c->d_bigsp_words);
 }
 
 template <class T>
@@ -161,9 +159,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
 
     int rc;
 #define UP(field, vec, what) do { rc = upload(c, &c->field, vec, what); if (rc != LDA_OK) return rc; } while (0)
-    UP(d_wkind, c->h_wkind, "word classes");
     UP(d_dense_alias_words, dense_alias, "dense-table words");
-    UP(d_mix_words, mix, "mixture words");
     UP(d_sparse_words, sparse, "sparse-row words");
     UP(d_compact_words, compact, "compaction words");
     UP(d_bigsp_words, bigsp, "big sparse words");

@@ -76,11 +76,9 @@ struct lda_ctx {
     // hybrid store / mixture proposal (Sec. 4.2 and 5); all null in the all-dense mode
     bool hybrid = false;
     int32_t H = 0;                       // word ids [0, H) own a dense n_kw row
-    uint8_t* d_wkind = nullptr;          // [V] bit 0: dense row, bit 1: dense proposal table
     int32_t* d_dense_alias_words = nullptr;  // words that draw from a dense K-bin table
     int32_t n_dense_alias = 0;
-    int32_t* d_mix_words = nullptr;      // words that draw from the mixture
-    int32_t n_mix = 0;
+    int32_t n_mix = 0;                   // words that draw from the mixture
     // the mixture words by list capacity: <= 64, <= 512, <= 4096, <= LDS maximum, larger
     int32_t* d_mix_class[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     int32_t n_mix_class[5] = {0, 0, 0, 0, 0};
@@ -104,7 +102,6 @@ struct lda_ctx {
     unsigned char* d_big_ws = nullptr;   // list memory of the workgroups that build big tables
     size_t big_ws_stride = 0;
     int32_t n_big_wg = 0;
-    int32_t* d_big_list = nullptr;       // [n_mix + 1] mixture words too big for LDS, [0] = count
     int32_t* d_scratch_rows = nullptr;   // dense scratch rows for the rebuild of big sparse words
     int32_t n_scratch_rows = 0;
     int32_t* d_bigsp_words = nullptr;    // sparse-row words rebuilt through scratch rows
@@ -114,7 +111,7 @@ struct lda_ctx {
     int32_t n_sortsp_class[4] = {0, 0, 0, 0};
     int64_t total_list = 0, total_hash = 0;
     std::vector<int32_t> h_wcount;       // corpus frequency of every word
-    std::vector<uint8_t> h_wkind;
+    std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table
     std::vector<uint32_t> h_sp_off, h_hs_off;
     // scratch
     double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
@@ -128,7 +125,6 @@ struct lda_ctx {
 namespace lda {
 
 int fail(lda_ctx* c, int code, const char* fmt, ...);
-void set_init_error(const char* msg);
 
 #define LDA_HIP(ctx, call)                                                              \
     do {                                                                                \
