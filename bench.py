@@ -51,14 +51,14 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def cpu_baseline(cfg, doff, words, mh_steps, sample_docs):
+def cpu_baseline(cfg, doff, words, mh_steps, sample_docs, dense_alias_min_count=0):
     """The oracle as it stands on the first `sample_docs` documents (same V, K)."""
     import oracle
     D = min(sample_docs, len(doff) - 1)
     sdoff = np.ascontiguousarray(doff[: D + 1])
     swords = np.ascontiguousarray(words[: int(sdoff[-1])])
     o = oracle.Oracle(sdoff, swords, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                      lazy_alias=True)
+                      dense_alias_min_count=dense_alias_min_count, lazy_alias=True)
     t0 = time.perf_counter()
     o.build_alias()
     o.sweep(mh_steps)
@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--chunk-tokens", type=int, default=0)
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--dense-alias-min-count", type=int, default=-1, help="c1-c3: words with "
+                    "fewer tokens draw from the mixture word-proposal (Sec. 4.2) instead of a "
+                    "dense K-bin table; 0 = dense tables for every word")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a "
@@ -124,6 +127,9 @@ def main():
             max(dense_rows, 0), hybrid["dense_alias_min_count"])
         del cnt, tail
         args.no_cpu_baseline = True  # the oracle keeps a dense V x K table
+    elif args.dense_alias_min_count > 0:
+        hybrid = dict(dense_rows=0, dense_alias_min_count=args.dense_alias_min_count)
+        store = "dense n_kw, mixture proposal below count %d" % args.dense_alias_min_count
 
     stream = torch.cuda.Stream()
     t0 = time.perf_counter()
@@ -216,7 +222,8 @@ def main():
     g.close()
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_docs or {"c1": 1000, "c2": 3000, "c3": 30000}[args.workload]
-        out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample)
+        out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample,
+                                           hybrid.get("dense_alias_min_count", 0))
     print(json.dumps(out))
 
 

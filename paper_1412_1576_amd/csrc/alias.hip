@@ -72,9 +72,7 @@ struct SparseSink {
     __device__ __forceinline__ void store(int32_t i, uint32_t split, uint32_t,
                                           const Loaded& v) const
     {
-        out[2 * (size_t)i] =
-            make_uint4(split, (uint32_t)v.t_own, (uint32_t)v.t_other, (uint32_t)v.n_own);
-        out[2 * (size_t)i + 1] = make_uint4((uint32_t)v.n_other, 0u, 0u, 0u);
+        out[i] = pack_mix_bin(split, v.t_own, v.t_other, v.n_own, v.n_other);
     }
 };
 
@@ -176,7 +174,7 @@ __device__ __forceinline__ void mix_table(const MixArgs& a, int32_t w, unsigned 
     }
     const size_t off = a.sp_off[w];
     SparseSrc src{a.sp_topic + off, a.sp_count + off, a.nk, a.betabar};
-    SparseSink sink{a.ma + 2 * off, a.sp_topic + off, a.sp_count + off};
+    SparseSink sink{a.ma + off, a.sp_topic + off, a.sp_count + off};
     uint64_t QS;
     uint32_t C;
     build_alias_table<GLOBAL>(n, src, sink, lists, a.use_cache != 0, QS, C);

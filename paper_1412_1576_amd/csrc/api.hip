@@ -115,6 +115,10 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
         if (dense_alias_w) {
             dense_alias.push_back(w);
         } else {
+            if ((uint32_t)cw >> kMixCountBits)
+                return fail(c, LDA_ERR_UNSUPPORTED,
+                            "lda_init: word %d has %d tokens; a word with 2^%u tokens or more must "
+                            "draw from a dense table (dense_alias_min_count)", w, cw, kMixCountBits);
             const int32_t cap = std::min(cw, K);
             list_total += (uint64_t)cap;
             mix.push_back(w);
@@ -181,8 +185,8 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     AL(d_sp_count, list_total, "sparse rows");
     AL(d_sp_nnz, V, "sparse rows");
     AL(d_hs, hash_total, "hash rows");
-    AL(d_ma, 2 * list_total, "mixture tables");
-    AL(d_beta_alias, K, "beta table");
+    AL(d_ma, list_total, "mixture tables");
+    AL(d_beta_alias, (size_t)K + 2, "beta table");  // read in aligned pairs
     AL(d_beta_hdr, 2, "beta table");
     LDA_HIP(c, hipMemsetAsync(c->d_sp_nnz, 0, sizeof(int32_t) * (size_t)V, c->stream));
     // global list memory for tables too large for LDS
@@ -613,13 +617,14 @@ int lda_get_sparse_table(lda_ctx* c, int32_t w, int32_t cap_entries, int32_t* n,
     if (cap) *cap = m.y;
     if (mass) *mass = ((uint64_t)m.w << 32) | m.z;
     if ((int32_t)m.x <= cap_entries && m.x > 0 && topics && split && alias_topic) {
-        std::vector<uint4> e(2 * (size_t)m.x);
-        LDA_HIP(c, hipMemcpy(e.data(), c->d_ma + 2 * (size_t)c->h_sp_off[w],
+        std::vector<uint4> e((size_t)m.x);
+        LDA_HIP(c, hipMemcpy(e.data(), c->d_ma + (size_t)c->h_sp_off[w],
                              sizeof(uint4) * e.size(), hipMemcpyDeviceToHost));
         for (uint32_t i = 0; i < m.x; ++i) {
-            split[i] = e[2 * i].x;
-            topics[i] = (int32_t)e[2 * i].y;
-            alias_topic[i] = (int32_t)e[2 * i].z;
+            int32_t cnt;
+            split[i] = e[i].x;
+            unpack_mix_bin(e[i], true, topics[i], cnt);
+            unpack_mix_bin(e[i], false, alias_topic[i], cnt);
         }
     }
     return LDA_OK;

@@ -92,7 +92,7 @@ struct lda_ctx {
     int32_t* d_sp_nnz = nullptr;         // [V] entries in use
     uint32_t* d_hs_off = nullptr;        // [V+1] first hash slot of word w (power-of-two capacity)
     uint2* d_hs = nullptr;               // (topic, count) slots, topic = -1: empty
-    uint4* d_ma = nullptr;               // mixture tables: two uint4 per list entry
+    uint4* d_ma = nullptr;               // mixture tables: one packed bin per list entry
     // one 32-byte record per word, [2w] = (entries n, capacity C, QS low, QS high) rewritten by
     // every table build, [2w+1] = (list offset, hash offset, log2 hash slots, kind) fixed
     uint4* d_metaA = nullptr;            // [2V]
@@ -148,6 +148,25 @@ int max_lds_table_entries();  // largest alias table built in LDS
 __host__ __device__ inline uint32_t row_hash_slot(int32_t t, uint32_t lg)
 {
     return ((uint32_t)t * 0x9E3779B1u) >> (32u - lg);
+}
+
+// A bin of a mixture word's own table in 16 bytes: the split height and, for each
+// of its two outcomes, the topic (20 bits) and the word's count of it (28 bits).
+constexpr uint32_t kMixTopicBits = 20, kMixCountBits = 28;
+__host__ __device__ inline uint4 pack_mix_bin(uint32_t split, int32_t t_own, int32_t t_other,
+                                              int32_t n_own, int32_t n_other)
+{
+    return make_uint4(split, (uint32_t)t_own | ((uint32_t)n_own << kMixTopicBits),
+                      (uint32_t)t_other | ((uint32_t)n_other << kMixTopicBits),
+                      ((uint32_t)n_own >> 12) | (((uint32_t)n_other >> 12) << 16));
+}
+__host__ __device__ inline void unpack_mix_bin(const uint4& e, bool own, int32_t& topic,
+                                               int32_t& count)
+{
+    const uint32_t sel = own ? e.y : e.z;
+    const uint32_t hi = own ? (e.w & 0xFFFFu) : (e.w >> 16);
+    topic = (int32_t)(sel & ((1u << kMixTopicBits) - 1u));
+    count = (int32_t)((sel >> kMixTopicBits) | (hi << 12));
 }
 int launch_sweep(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile

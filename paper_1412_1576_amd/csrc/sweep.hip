@@ -175,29 +175,43 @@ __device__ __forceinline__ void mh_chains(const SweepArgs& A, const DocView (&do
 }
 
 // ---- hybrid store: the word side of a token ------------------------------------------
-struct WordView {
-    uint32_t kind;   // bit 0: dense n_kw row, bit 1: dense proposal table
-    uint32_t n, C;   // entries and capacity of the word's own table
-    uint64_t QS;     // integer mass of the sparse term (mixture form)
-    uint32_t list_off, hs_off, lg;
-    size_t wk;       // w * K (dense row / dense table offset)
+// STORE: 0 = every word has a dense row and a dense table (mh_chains above);
+// 1 = dense rows only, some words draw from the mixture; 2 = sparse rows as well.
+struct WordSide {
+    const uint4* tab;  // the word's own table: K dense bins, or its mixture bins
+    const void* row;   // dense n_kw row (int32[K]), or hash row (uint2[2^lg]) in store 2
+    uint32_t n, C;     // bins and capacity of the own table
+    uint32_t kind;     // bit 0: dense n_kw row, bit 1: dense proposal table
+    uint32_t lg;
+    uint64_t QS;       // integer mass of the sparse term (mixture form)
 };
 
-__device__ __forceinline__ WordView load_word(const SweepArgs& A, int32_t w)
+template <int STORE>
+__device__ __forceinline__ WordSide load_word(const SweepArgs& A, int32_t w)
 {
     const uint4 a = A.metaA[2 * (size_t)w], b = A.metaB[2 * (size_t)w];  // one 32-byte record
-    WordView v;
-    v.n = a.x; v.C = a.y; v.QS = ((uint64_t)a.w << 32) | a.z;
-    v.list_off = b.x; v.hs_off = b.y; v.lg = b.z; v.kind = b.w;
-    v.wk = (size_t)w * (size_t)A.K;
+    WordSide v;
+    v.kind = b.w;
+    v.lg = b.z;
+    v.C = a.y;
+    v.QS = ((uint64_t)a.w << 32) | a.z;
+    const size_t wk = (size_t)w * (size_t)A.K;
+    const bool dense_tab = (b.w & 2u) != 0;
+    v.n = dense_tab ? (uint32_t)A.K : a.x;
+    v.tab = dense_tab ? A.alias + wk : A.ma + b.x;
+    if (STORE == 2 && !(b.w & 1u))
+        v.row = A.hs + b.y;
+    else
+        v.row = A.nkw + wk;
     return v;
 }
 
 // n_kw[w][t]: dense row, or the word's hash row (Sec. 5)
-__device__ __forceinline__ int32_t nkw_lookup(const SweepArgs& A, const WordView& v, int32_t t)
+template <int STORE>
+__device__ __forceinline__ int32_t nkw_lookup(const WordSide& v, int32_t t)
 {
-    if (v.kind & 1u) return A.nkw[v.wk + (size_t)t];
-    const uint2* __restrict__ row = A.hs + v.hs_off;
+    if (STORE != 2 || (v.kind & 1u)) return static_cast<const int32_t*>(v.row)[t];
+    const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
     const uint32_t mask = (1u << v.lg) - 1u;
     uint32_t s = row_hash_slot(t, v.lg);
     for (uint32_t i = 0; i <= mask; ++i) {
@@ -211,75 +225,89 @@ __device__ __forceinline__ int32_t nkw_lookup(const SweepArgs& A, const WordView
 
 // Chains with the hybrid word side: dense tables for the head words, the
 // sparsified mixture (Sec. 4.2) for the others.  Same structure as mh_chains.
-template <int T, class DocView>
+// The three forms of a word step (dense table, sparse term, shared beta term)
+// differ only in the address of the one 16-byte record they gather and in how it
+// is decoded, so every lane issues the same load.
+template <int T, int STORE, class DocView>
 __device__ __forceinline__ void mh_chains_hybrid(const SweepArgs& A, const DocView (&doc)[T],
                                                  const uint32_t (&own)[T], const int32_t (&w)[T],
                                                  const uint32_t (&g)[T], int32_t (&s)[T])
 {
 #pragma clang fp contract(off)
-    const int32_t K = A.K;
+    const uint32_t K = (uint32_t)A.K;
     const uint64_t QB = A.beta_hdr[0];
     const uint32_t Cb = (uint32_t)A.beta_hdr[1];
-    WordView wv[T];
+    const uint4* __restrict__ beta_pairs = reinterpret_cast<const uint4*>(A.beta_alias);
+    WordSide wv[T];
     int32_t z0[T], nds[T], nws[T], nks[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         doc[u].token(own[u], z0[u], nds[u]);
         s[u] = z0[u];
-        wv[u] = load_word(A, w[u]);
-        nws[u] = nkw_lookup(A, wv[u], z0[u]);
+        wv[u] = load_word<STORE>(A, w[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        nws[u] = nkw_lookup<STORE>(wv[u], z0[u]);
         nks[u] = A.nk[z0[u]];
     }
     for (int32_t j = 0; j < A.mh_steps; ++j) {
         const bool word_step = (A.mode == 0) ? ((j & 1) == 0) : (A.mode == 1);
         uint32_t x2[T];
         int32_t t[T], ndt[T], nwt[T], nkt[T];
+        if (word_step) {
+            uint32_t bin[T], rr[T], form[T];  // 0 dense table, 1 sparse term, 2 beta term
+            uint4 e[T];
 #pragma unroll
-        for (int u = 0; u < T; ++u) {
-            uint32_t x[4];
-            philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
-            x2[u] = x[2];
-            if (word_step) {
-                if (wv[u].kind & 2u) {
-                    const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-                    const uint32_t rr = mulhi32(x[1], wv[u].C);
-                    const uint4 e = A.alias[wv[u].wk + bin];
-                    const bool keep = rr < e.x;
-                    t[u] = keep ? (int32_t)bin : (int32_t)e.y;
-                    nwt[u] = keep ? (int32_t)e.z : (int32_t)e.w;
-                } else {
-                    // pick the term by its integer mass, then draw from that term's table
-                    const double u3 = unit_open(x[3]);
-                    if (u3 * (double)(wv[u].QS + QB) < (double)wv[u].QS) {
-                        const uint32_t bin = mulhi32(x[0], wv[u].n);
-                        const uint32_t rr = mulhi32(x[1], wv[u].C);
-                        const uint4* __restrict__ e = A.ma + 2 * ((size_t)wv[u].list_off + bin);
-                        const uint4 e0 = e[0], e1 = e[1];
-                        const bool keep = rr < e0.x;
-                        t[u] = keep ? (int32_t)e0.y : (int32_t)e0.z;
-                        nwt[u] = keep ? (int32_t)e0.w : (int32_t)e1.x;
-                    } else {
-                        const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-                        const uint32_t rr = mulhi32(x[1], Cb);
-                        const uint2 e = A.beta_alias[bin];
-                        t[u] = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
-                        nwt[u] = nkw_lookup(A, wv[u], t[u]);
-                    }
-                }
+            for (int u = 0; u < T; ++u) {
+                uint32_t x[4];
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                x2[u] = x[2];
+                // mixture: pick the term by its integer mass, then draw from that term's table
+                const double u3 = unit_open(x[3]);
+                const bool sparse_term = u3 * (double)(wv[u].QS + QB) < (double)wv[u].QS;
+                form[u] = (wv[u].kind & 2u) ? 0u : (sparse_term ? 1u : 2u);
+                const bool beta_term = form[u] == 2u;
+                bin[u] = mulhi32(x[0], beta_term ? K : wv[u].n);
+                rr[u] = mulhi32(x[1], beta_term ? Cb : wv[u].C);
+                const uint4* p = beta_term ? beta_pairs + (bin[u] >> 1) : wv[u].tab + bin[u];
+                e[u] = *p;
+            }
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                // beta table: two 8-byte bins per record
+                const bool odd = (form[u] == 2u) && (bin[u] & 1u);
+                const bool keep = rr[u] < (odd ? e[u].z : e[u].x);
+                int32_t tm, nm;
+                unpack_mix_bin(e[u], keep, tm, nm);
+                const int32_t td = keep ? (int32_t)bin[u] : (int32_t)(odd ? e[u].w : e[u].y);
+                t[u] = (form[u] == 1u) ? tm : td;
+                nwt[u] = (form[u] == 1u) ? nm : (keep ? (int32_t)e[u].z : (int32_t)e[u].w);
+                nkt[u] = A.nk[t[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                if (form[u] == 2u) nwt[u] = nkw_lookup<STORE>(wv[u], t[u]);
                 ndt[u] = doc[u].count(t[u]);
-            } else {
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < T; ++u) {
+                uint32_t x[4];
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                x2[u] = x[2];
                 const double u0 = unit_open(x[0]);
                 const double Ld = (double)doc[u].L;
                 if (u0 * (Ld + A.alphabar) < Ld) {
                     doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[u], ndt[u]);
                 } else {
-                    t[u] = (int32_t)mulhi32(x[1], (uint32_t)K);
+                    t[u] = (int32_t)mulhi32(x[1], K);
                     ndt[u] = doc[u].count(t[u]);
                 }
+                nkt[u] = A.nk[t[u]];
                 nwt[u] = nws[u];
-                if (t[u] != s[u]) nwt[u] = nkw_lookup(A, wv[u], t[u]);
+                if (t[u] != s[u]) nwt[u] = nkw_lookup<STORE>(wv[u], t[u]);
             }
-            nkt[u] = A.nk[t[u]];
         }
 #pragma unroll
         for (int u = 0; u < T; ++u) {
@@ -312,7 +340,7 @@ __device__ __forceinline__ void mh_chains_hybrid(const SweepArgs& A, const DocVi
 
 // T = tokens per thread; a tile has at most T * blockDim.x tokens.  MAXB bounds
 // the block size so that small blocks may use more registers per thread.
-template <int T, int MAXB, bool HYBRID>
+template <int T, int MAXB, int STORE>
 __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
 {
     extern __shared__ int32_t smem[];
@@ -341,8 +369,8 @@ __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
         own[u] = (uint32_t)(i - b);
         w[u] = A.word[g[u]];
     }
-    if constexpr (HYBRID)
-        mh_chains_hybrid<T>(A, doc, own, w, g, s);
+    if constexpr (STORE != 0)
+        mh_chains_hybrid<T, STORE>(A, doc, own, w, g, s);
     else
         mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
@@ -350,7 +378,7 @@ __global__ __launch_bounds__(MAXB) void sweep_tiles_kernel(SweepArgs A)
         if (live[u]) A.znew[g[u]] = s[u];
 }
 
-template <bool HYBRID>
+template <int STORE>
 __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
 {
     constexpr int T = 2;
@@ -377,8 +405,8 @@ __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
             g[u] = (uint32_t)(tok0 + i);
             w[u] = A.word[g[u]];
         }
-        if constexpr (HYBRID)
-            mh_chains_hybrid<T>(A, doc, own, w, g, s);
+        if constexpr (STORE != 0)
+            mh_chains_hybrid<T, STORE>(A, doc, own, w, g, s);
         else
             mh_chains<T>(A, doc, own, w, g, s);
 #pragma unroll
@@ -387,10 +415,10 @@ __global__ __launch_bounds__(1024) void sweep_long_docs_kernel(SweepArgs A)
     }
 }
 
-template <int T, int MAXB, bool HYBRID>
+template <int T, int MAXB, int STORE>
 int launch_tiles_tb(lda_ctx* c, const SweepArgs& A, size_t lds)
 {
-    auto kern = sweep_tiles_kernel<T, MAXB, HYBRID>;
+    auto kern = sweep_tiles_kernel<T, MAXB, STORE>;
     if (lds > 48 * 1024)
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -399,23 +427,23 @@ int launch_tiles_tb(lda_ctx* c, const SweepArgs& A, size_t lds)
     return LDA_OK;
 }
 
-template <int T, bool HYBRID>
+template <int T, int STORE>
 int launch_tiles_t(lda_ctx* c, const SweepArgs& A, size_t lds)
 {
-    if (c->sweep_block <= 256) return launch_tiles_tb<T, 256, HYBRID>(c, A, lds);
-    if (c->sweep_block <= 512) return launch_tiles_tb<T, 512, HYBRID>(c, A, lds);
-    return launch_tiles_tb<T, 1024, HYBRID>(c, A, lds);
+    if (c->sweep_block <= 256) return launch_tiles_tb<T, 256, STORE>(c, A, lds);
+    if (c->sweep_block <= 512) return launch_tiles_tb<T, 512, STORE>(c, A, lds);
+    return launch_tiles_tb<T, 1024, STORE>(c, A, lds);
 }
 
-template <bool HYBRID>
+template <int STORE>
 int launch_tiles(lda_ctx* c, const SweepArgs& A, size_t lds)
 {
     const int tpt = (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
-    if (tpt <= 1) return launch_tiles_t<1, HYBRID>(c, A, lds);
-    if (tpt <= 2) return launch_tiles_t<2, HYBRID>(c, A, lds);
-    if (tpt <= 4) return launch_tiles_t<4, HYBRID>(c, A, lds);
-    if (tpt <= 6) return launch_tiles_t<6, HYBRID>(c, A, lds);
-    if (tpt <= 8) return launch_tiles_t<8, HYBRID>(c, A, lds);
+    if (tpt <= 1) return launch_tiles_t<1, STORE>(c, A, lds);
+    if (tpt <= 2) return launch_tiles_t<2, STORE>(c, A, lds);
+    if (tpt <= 4) return launch_tiles_t<4, STORE>(c, A, lds);
+    if (tpt <= 6) return launch_tiles_t<6, STORE>(c, A, lds);
+    if (tpt <= 8) return launch_tiles_t<8, STORE>(c, A, lds);
     return fail(c, LDA_ERR_ARG, "sweep: more than 8 tokens per thread (tile %d, block %d)",
                 c->chunk_tokens, c->sweep_block);
 }
@@ -466,36 +494,28 @@ static SweepArgs make_sweep_args(lda_ctx* c, int32_t mh_steps)
     return A;
 }
 
-int launch_sweep(lda_ctx* c, int32_t mh_steps)
+template <int STORE>
+static int launch_sweep_store(lda_ctx* c, int32_t mh_steps)
 {
     const SweepArgs A = make_sweep_args(c, mh_steps);
     const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
     if (c->n_chunks > 0) {
-        const int rc = launch_tiles<false>(c, A, lds);
+        const int rc = launch_tiles<STORE>(c, A, lds);
         if (rc != LDA_OK) return rc;
     }
     if (c->n_long > 0) {
-        hipLaunchKernelGGL(sweep_long_docs_kernel<false>, dim3(c->n_long), dim3(1024), 0, c->stream,
-                           A);
+        hipLaunchKernelGGL(sweep_long_docs_kernel<STORE>, dim3(c->n_long), dim3(1024), 0,
+                           c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
     return LDA_OK;
 }
 
+int launch_sweep(lda_ctx* c, int32_t mh_steps) { return launch_sweep_store<0>(c, mh_steps); }
+
 int launch_sweep_hybrid(lda_ctx* c, int32_t mh_steps)
 {
-    const SweepArgs A = make_sweep_args(c, mh_steps);
-    const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
-    if (c->n_chunks > 0) {
-        const int rc = launch_tiles<true>(c, A, lds);
-        if (rc != LDA_OK) return rc;
-    }
-    if (c->n_long > 0) {
-        hipLaunchKernelGGL(sweep_long_docs_kernel<true>, dim3(c->n_long), dim3(1024), 0, c->stream,
-                           A);
-        LDA_HIP(c, hipGetLastError());
-    }
-    return LDA_OK;
+    return c->H == c->V ? launch_sweep_store<1>(c, mh_steps) : launch_sweep_store<2>(c, mh_steps);
 }
 
 // ---- n_kd accessor: the row exactly as the sweep kernels form it -------------------
