@@ -55,7 +55,8 @@ void dev_free(T*& p)
 void free_all(lda_ctx* c)
 {
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
-    dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zw); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
+    dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
+    dev_free(c->d_row_items); dev_free(c->d_gather_pieces); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
     dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
@@ -355,7 +356,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_znew, (size_t)N, "z (next)"));
     TRY(dev_alloc(c, &c->d_gid, (size_t)N, "word-major order"));
     TRY(dev_alloc(c, &c->d_wpos, (size_t)N, "word-major positions"));
-    TRY(dev_alloc(c, &c->d_zw, (size_t)N, "word-major z"));
+    TRY(dev_alloc(c, &c->d_zt, (size_t)N, "word-major z"));
+    c->zt_ints = (size_t)N;
     TRY(dev_alloc(c, &c->d_woff, (size_t)V + 1, "word offsets"));
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
     TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));
@@ -398,6 +400,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (hybrid) {
         TRY(setup_hybrid(c, woff));
         any_dense_alias = c->n_dense_alias > 0;
+    } else {
+        TRY(setup_split_sweep(c, woff));
     }
     TRY(dev_alloc(c, &c->d_alias, any_dense_alias ? VK : 1, "alias tables"));
     std::vector<RebuildTile> tiles;
@@ -427,7 +431,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY_HIP(hipStreamSynchronize(c->stream));
 #undef TRY
 #undef TRY_HIP
-    dev_free(c->d_gid);  // only wpos is needed from here on
+    if (hybrid) dev_free(c->d_gid);  // only the two-pass sweep walks the word-major order
     c->state = COUNTS_VALID;
     c->sweep_index = 0;
     *out = c;
@@ -460,7 +464,14 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
     if (c->state != ALIAS_VALID)
         return fail(c, LDA_ERR_STATE, "lda_sweep: needs fresh alias tables (call lda_build_alias)");
     if (c->sweep_index == 0xFFFFFFFEu) return fail(c, LDA_ERR_STATE, "lda_sweep: sweep index exhausted");
-    const int rc = c->hybrid ? launch_sweep_hybrid(c, mh_steps) : launch_sweep(c, mh_steps);
+    int rc;
+    if (split_sweep_supported(c, mh_steps)) {
+        rc = launch_sweep_split(c, mh_steps);
+    } else {
+        rc = c->hybrid ? launch_sweep_hybrid(c, mh_steps) : launch_sweep(c, mh_steps);
+        c->zt_current = false;  // the fused kernels write the doc-major assignment only
+        c->td_valid = false;
+    }
     if (rc != LDA_OK) return rc;
     std::swap(c->d_z, c->d_znew);
     c->sweep_index += 1;
@@ -518,6 +529,8 @@ int lda_set_z(lda_ctx* c, const int32_t* z, int64_t next_sweep_index)
     if (rc != LDA_OK) return rc;
     if (!ok) return fail(c, LDA_ERR_ARG, "lda_set_z: a topic is outside [0, K)");
     std::swap(c->d_z, c->d_znew);
+    c->zt_current = false;
+    c->td_valid = false;
     c->sweep_index = (uint32_t)next_sweep_index;
     c->state = SWEPT;
     return LDA_OK;

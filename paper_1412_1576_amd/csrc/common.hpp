@@ -46,9 +46,25 @@ struct lda_ctx {
     int32_t* d_z = nullptr;     // [N] snapshot assignment
     int32_t* d_znew = nullptr;  // [N] next assignment
     // word-major view
-    int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order (init only)
+    int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order
     int32_t* d_wpos = nullptr;  // [N] word-major position of token g (inverse of gid)
-    int32_t* d_zw = nullptr;    // [N] z in word-major order, refreshed by every count rebuild
+    // Word-major token records of 2^zt_shift ints: [0] the token's z, [1 + i] the topic that
+    // doc step i of the coming sweep proposes for it (when td_valid).
+    int32_t* d_zt = nullptr;
+    size_t zt_ints = 0;         // allocated ints
+    int32_t zt_shift = 0;
+    bool zt_current = false;    // record [0] equals d_z
+    bool td_valid = false;      // the stored doc proposals are those of sweep td_sweep, drawn
+    uint32_t td_sweep = 0;      //   from d_z, for a chain of td_nw word and td_nd doc steps
+    int32_t td_nw = 0, td_nd = 0;
+    // Word-pass output, word-major, 2^rec_shift ints per token (sweep_split.hip)
+    int32_t* d_rec = nullptr;
+    size_t rec_ints = 0;
+    // Work lists of the word pass: items (w, p0, n, 0) whose rows are staged in LDS, and
+    // pieces (w0, w1, p0, n) of several short words whose rows are gathered
+    int4* d_row_items = nullptr;
+    int4* d_gather_pieces = nullptr;
+    int32_t n_row_items = 0, n_gather_pieces = 0;
     int32_t* d_woff = nullptr;  // [V+1] segment offsets
     // model
     int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)
@@ -169,6 +185,10 @@ __host__ __device__ inline void unpack_mix_bin(const uint4& e, bool own, int32_t
     count = (int32_t)((sel >> kMixTopicBits) | (hi << 12));
 }
 int launch_sweep(lda_ctx* c, int32_t mh_steps);
+// Two-pass sweep (word pass over word-major tokens, doc pass over document tiles)
+bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps);
+int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);
+int launch_sweep_split(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);

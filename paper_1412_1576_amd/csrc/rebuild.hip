@@ -28,7 +28,8 @@ constexpr int kScatterBlock = 1024;
 
 __global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restrict__ z,
                                                          const int32_t* __restrict__ wpos,
-                                                         int64_t N, int32_t* __restrict__ zw)
+                                                         int64_t N, int32_t* __restrict__ zw,
+                                                         int32_t sh)
 {
     const int64_t per_xcd = (N + kXcds - 1) / kXcds;
     const int xcd = blockIdx.x % kXcds;
@@ -39,14 +40,15 @@ __global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restr
 #pragma unroll
     for (int u = 0; u < kScatterPerThread; ++u) {
         const int64_t g = base + u * (int64_t)blockDim.x + threadIdx.x;
-        if (g < hi) zw[__builtin_nontemporal_load(&wpos[g])] = __builtin_nontemporal_load(&z[g]);
+        if (g < hi)
+            zw[(size_t)__builtin_nontemporal_load(&wpos[g]) << sh] = __builtin_nontemporal_load(&z[g]);
     }
 }
 
 // blockIdx.x: tile; blockIdx.y: range of `span` topics (one range when the row fits LDS)
 __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __restrict__ tiles,
                                                          const int32_t* __restrict__ zw,
-                                                         int32_t K, int32_t span,
+                                                         int32_t sh, int32_t K, int32_t span,
                                                          int32_t* __restrict__ nkw)
 {
     extern __shared__ int32_t hist[];
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
     for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
     __syncthreads();
     for (int32_t p = t.p0 + tid; p < t.p1; p += nt) {
-        const uint32_t r = (uint32_t)(zw[p] - k0);
+        const uint32_t r = (uint32_t)(zw[(size_t)p << sh] - k0);
         if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
     }
     __syncthreads();
@@ -117,14 +119,16 @@ namespace {
 int launch_dense_rows(lda_ctx* c)
 {
     const int32_t K = c->K;
-    {
+    if (!c->zt_current) {  // the sweep's doc pass may have written the new assignment already
         const int64_t per_xcd = (c->N + kXcds - 1) / kXcds;
         const int64_t per_block = kScatterBlock * kScatterPerThread;
         const int64_t blocks = ((per_xcd + per_block - 1) / per_block) * kXcds;
         hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(kScatterBlock), 0, c->stream,
-                           c->d_z, c->d_wpos, c->N, c->d_zw);
+                           c->d_z, c->d_wpos, c->N, c->d_zt, c->zt_shift);
+        LDA_HIP(c, hipGetLastError());
+        c->zt_current = true;
+        c->td_valid = false;  // any stored doc proposals belong to another assignment
     }
-    LDA_HIP(c, hipGetLastError());
     if (c->n_tiles == 0) return LDA_OK;
     const int32_t nr = (K + max_rebuild_topics() - 1) / max_rebuild_topics();
     const int32_t span = (((K + nr - 1) / nr) + 63) / 64 * 64;
@@ -138,7 +142,8 @@ int launch_dense_rows(lda_ctx* c)
         LDA_HIP(c, hipGetLastError());
     }
     hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
-                       dim3(span <= 512 ? 256 : 1024), lds, c->stream, c->d_tiles, c->d_zw, K, span,
+                       dim3(span <= 512 ? 256 : 1024), lds, c->stream, c->d_tiles, c->d_zt,
+                       c->zt_shift, K, span,
                        c->d_nkw);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
@@ -249,7 +254,7 @@ __device__ __forceinline__ uint32_t log2_pow2(uint32_t x) { return 31u - (uint32
 // fill the hash row.
 __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     const int32_t* __restrict__ words, int32_t P, const int32_t* __restrict__ woff,
-    const int32_t* __restrict__ zw,
+    const int32_t* __restrict__ zw, int32_t sh,
     const uint32_t* __restrict__ sp_off, int32_t* __restrict__ sp_topic,
     int32_t* __restrict__ sp_count, int32_t* __restrict__ sp_nnz,
     const uint32_t* __restrict__ hs_off, uint2* __restrict__ hs)
@@ -268,7 +273,7 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     }
     int32_t Q = 2;  // sort size: smallest power of two >= c
     while (Q < c) Q <<= 1;
-    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? zw[p0 + i] : kSortPad;
+    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? zw[(size_t)(p0 + i) << sh] : kSortPad;
     __syncthreads();
     for (int32_t k = 2; k <= Q; k <<= 1) {
         for (int32_t j = k >> 1; j > 0; j >>= 1) {
@@ -325,7 +330,8 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
 __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __restrict__ words,
                                                            int32_t n_words, int32_t tile,
                                                            const int32_t* __restrict__ woff,
-                                                           const int32_t* __restrict__ zw, int32_t K,
+                                                           const int32_t* __restrict__ zw,
+                                                           int32_t sh, int32_t K,
                                                            int32_t* __restrict__ scratch)
 {
     const int32_t wi = blockIdx.y;
@@ -336,7 +342,7 @@ __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __rest
     for (int32_t b = p0 + (int32_t)blockIdx.x * tile; b < p1; b += (int32_t)gridDim.x * tile) {
         const int32_t e = (b + tile < p1) ? b + tile : p1;
         for (int32_t p = b + (int32_t)threadIdx.x; p < e; p += (int32_t)blockDim.x)
-            atomicAdd(&row[zw[p]], 1);
+            atomicAdd(&row[zw[(size_t)p << sh]], 1);
     }
 }
 
@@ -406,7 +412,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         const int threads = P <= 64 ? 64 : (P <= 512 ? 256 : 1024);
         hipLaunchKernelGGL(sparse_rows_sort_kernel, dim3(c->n_sortsp_class[cl]), dim3(threads), lds,
-                           c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_zw,
+                           c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_zt, c->zt_shift,
                            c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz, c->d_hs_off,
                            c->d_hs);
         LDA_HIP(c, hipGetLastError());
@@ -415,7 +421,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
     for (int32_t b0 = 0; b0 < c->n_bigsp; b0 += c->n_scratch_rows) {
         const int32_t nb = std::min(c->n_scratch_rows, c->n_bigsp - b0);
         hipLaunchKernelGGL(scratch_hist_kernel, dim3(64, nb), dim3(256), 0, c->stream,
-                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zw, K,
+                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zt, c->zt_shift, K,
                            c->d_scratch_rows);
         LDA_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(scratch_compact_kernel, dim3(nb), dim3(1024), 0, c->stream,

@@ -1,0 +1,702 @@
+// Two-pass form of the cycle Metropolis-Hastings sweep (LightLDA Sec. 4.2-4.3, Eq. 6-13).
+//
+// A proposal never depends on the chain's current state: a word-proposal draw is a
+// function of the word's table and the token's random numbers (Fig. 2), a
+// doc-proposal draw of the document's snapshot assignment (Eq. 12).  The word side of
+// a token's chain -- its alias draws and every n_kw its ratios will need -- can
+// therefore be evaluated before the accept tests, in word-major order, where all
+// accesses of a word fall into that word's own rows:
+//
+//   word pass  word-major.  Frequent words: a workgroup stages the word's n_kw row and
+//              its table in LDS and serves a run of the word's tokens from there
+//              (one coalesced read of the rows per 16384 tokens instead of three random
+//              128-byte lines per token).  Short words: the rows are gathered; the
+//              word's tokens are processed together, so its lines are reused in L2.
+//              Output: one record per token (n_kw at its snapshot topic, the proposed
+//              topic and its n_kw for every word step, n_kw at every doc proposal).
+//   doc pass   document tiles in LDS as in the fused kernel; the word side of a token is
+//              the one record gathered from its word-major position.  Runs every accept
+//              test (Eq. 8, 11) in order and writes the new assignment.  Its tail draws
+//              the doc proposals of the NEXT sweep from the tile's new assignment and
+//              writes (z, proposals) to the token's word-major record, which is what
+//              the next word pass and the count rebuild read: no separate scatter pass.
+//
+// The arithmetic, the random numbers and their use are those of the fused kernel
+// (sweep.hip), so the result is bit-identical.
+#include <algorithm>
+
+#include "common.hpp"
+#include "doc_tile.hpp"
+
+namespace lda {
+
+namespace {
+
+constexpr int kXcds = 8;
+constexpr int32_t kRowItemTokens = 16384;  // tokens a workgroup serves from one staging of the rows
+constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
+constexpr int32_t kPieceTokens = 4096;     // tokens of a gather piece
+constexpr int32_t kPieceWords = 4096;      // words of a gather piece (their offsets sit in LDS)
+
+constexpr int pow2_shift(int n)
+{
+    int s = 0;
+    while ((1 << s) < n) ++s;
+    return s;
+}
+
+// Shape of a chain of NW word steps and ND doc steps: all word steps (ND = 0), all
+// doc steps (NW = 0), or alternating starting with a word step (Eq. 13).
+template <int NW, int ND>
+struct Chain {
+    static_assert(NW + ND >= 1 && (ND == 0 || NW == 0 || NW == ND || NW == ND + 1), "chain shape");
+    static constexpr int M = NW + ND;
+    static constexpr int zt_shift = pow2_shift(1 + ND);
+    static constexpr int rec_shift = pow2_shift(1 + 2 * NW + ND);
+    static constexpr int S = 1 << zt_shift;   // ints of a (z, doc proposals) record
+    static constexpr int R = 1 << rec_shift;  // ints of a word-pass record
+    __host__ __device__ static constexpr bool is_word(int j)
+    {
+        return ND == 0 ? true : (NW == 0 ? false : (j & 1) == 0);
+    }
+    __host__ __device__ static constexpr int index(int j) { return (ND == 0 || NW == 0) ? j : j / 2; }
+    __host__ __device__ static constexpr int word_step(int i) { return ND == 0 ? i : 2 * i; }
+    __host__ __device__ static constexpr int doc_step(int i) { return NW == 0 ? i : 2 * i + 1; }
+    // word-pass record: [0] n_kw[z0]; [1 + 2i], [2 + 2i] topic and n_kw of word step i;
+    // [1 + 2 NW + i] n_kw of doc step i's proposal
+    __host__ __device__ static constexpr int rec_topic(int i) { return 1 + 2 * i; }
+    __host__ __device__ static constexpr int rec_doc(int i) { return 1 + 2 * NW + i; }
+};
+
+template <int R>
+__device__ __forceinline__ void load_ints(const int32_t* __restrict__ p, int32_t (&v)[R])
+{
+    if constexpr (R == 1) {
+        v[0] = p[0];
+    } else if constexpr (R == 2) {
+        const int2 a = *reinterpret_cast<const int2*>(p);
+        v[0] = a.x; v[1] = a.y;
+    } else {
+#pragma unroll
+        for (int q = 0; q < R / 4; ++q) {
+            const int4 a = reinterpret_cast<const int4*>(p)[q];
+            v[4 * q] = a.x; v[4 * q + 1] = a.y; v[4 * q + 2] = a.z; v[4 * q + 3] = a.w;
+        }
+    }
+}
+
+template <int R>
+__device__ __forceinline__ void store_ints(int32_t* __restrict__ p, const int32_t (&v)[R])
+{
+    if constexpr (R == 1) {
+        p[0] = v[0];
+    } else if constexpr (R == 2) {
+        *reinterpret_cast<int2*>(p) = make_int2(v[0], v[1]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < R / 4; ++q)
+            reinterpret_cast<int4*>(p)[q] = make_int4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    }
+}
+
+struct SplitArgs {
+    const int32_t* z;
+    int32_t* znew;
+    const int32_t* doff;
+    const int32_t* chunk_doc;
+    const uint8_t* tokdoc;
+    const int32_t* wpos;
+    const int32_t* gid;
+    const int32_t* woff;
+    const int32_t* nkw;
+    const int32_t* nk;
+    const uint4* alias;  // (split, alias, n_kw[bin], n_kw[alias]) per bin
+    const uint32_t* cap;
+    int32_t* zt;
+    int32_t* rec;
+    const int4* row_items;
+    const int4* pieces;
+    int32_t n_chunks, n_row_items, n_pieces;
+    int32_t K, cap_tokens;
+    double alpha, beta, alphabar, betabar;
+    uint32_t seed_lo, seed_hi, sweep;
+    const int32_t* long_doc;
+    const int64_t* long_slot;
+    int32_t* long_keys;
+    int32_t* long_cnts;
+};
+
+// Workgroups are dealt to the 8 XCDs round-robin.  Handing each XCD one contiguous run of
+// the items keeps neighbouring items -- which touch neighbouring word-major records -- in
+// one L2.  Returns an index that may lie past the last item.
+__device__ __forceinline__ int32_t xcd_contiguous(int32_t n_items)
+{
+    const int32_t per = (n_items + kXcds - 1) / kXcds;
+    return (int32_t)(blockIdx.x % kXcds) * per + (int32_t)(blockIdx.x / kXcds);
+}
+
+unsigned xcd_grid(int32_t n_items) { return (unsigned)((n_items + kXcds - 1) / kXcds * kXcds); }
+
+// Eq. (9), (12): the topic of a random token of the document, or a uniform topic.
+// zat(j) is the snapshot topic of the document's j-th token.
+template <class ZAt>
+__device__ __forceinline__ int32_t doc_proposal(uint32_t x0, uint32_t x1, int32_t L, int32_t K,
+                                                double alphabar, ZAt zat)
+{
+#pragma clang fp contract(off)
+    const double u0 = unit_open(x0);
+    const double Ld = (double)L;
+    if (u0 * (Ld + alphabar) < Ld) return zat(mulhi32(x1, (uint32_t)L));
+    return (int32_t)mulhi32(x1, (uint32_t)K);
+}
+
+// (z, doc proposals of sweep A.sweep) of every token, from the doc-major snapshot.
+// Needed when no doc pass has left them behind: first sweep, after lda_set_z, or when
+// the chain shape changes.  One workgroup per document tile.
+template <int NW, int ND>
+__global__ __launch_bounds__(256) void doc_proposals_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    const int32_t c = xcd_contiguous(A.n_chunks);
+    if (c >= A.n_chunks) return;
+    const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
+    const int32_t tok0 = A.doff[d0], ntok = A.doff[d1] - tok0;
+    for (int32_t i = threadIdx.x; i < ntok; i += blockDim.x) {
+        const uint32_t g = (uint32_t)(tok0 + i);
+        int32_t row[C::S];
+#pragma unroll
+        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        row[0] = A.z[g];
+        if constexpr (ND > 0) {
+            const int32_t d = d0 + (int32_t)A.tokdoc[g];  // a long document is a tile of its own
+            const int32_t b = A.doff[d], L = A.doff[d + 1] - b;
+#pragma unroll
+            for (int k = 0; k < ND; ++k) {
+                uint32_t x[4];
+                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::doc_step(k), A.seed_lo, A.seed_hi, x);
+                row[1 + k] = doc_proposal(x[0], x[1], L, A.K, A.alphabar,
+                                          [&](uint32_t j) { return A.z[b + (int32_t)j]; });
+            }
+        }
+        store_ints<C::S>(A.zt + ((size_t)A.wpos[g] << C::zt_shift), row);
+    }
+}
+
+// ---- word pass -----------------------------------------------------------------------
+
+// One item = up to kRowItemTokens consecutive tokens of one word.
+template <int NW, int ND>
+__global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    extern __shared__ int32_t smem[];
+    uint2* __restrict__ tab = reinterpret_cast<uint2*>(smem);  // [K] (split, alias)
+    int32_t* __restrict__ row = smem + 2 * (size_t)A.K;        // [K] n_kw
+    const int32_t it_i = xcd_contiguous(A.n_row_items);
+    if (it_i >= A.n_row_items) return;
+    const int4 it = A.row_items[it_i];  // (w, p0, n, 0)
+    const int32_t K = A.K;
+    const size_t wk = (size_t)it.x * (size_t)K;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int32_t k = tid; k < K; k += nt) {
+        row[k] = A.nkw[wk + k];
+        if constexpr (NW > 0) {
+            const uint4 e = A.alias[wk + k];
+            tab[k] = make_uint2(e.x, e.y);
+        }
+    }
+    __syncthreads();
+    const uint32_t capw = A.cap[it.x];
+    for (int32_t i = tid; i < it.z; i += nt) {
+        const int32_t p = it.y + i;
+        int32_t zt[C::S], out[C::R];
+        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+#pragma unroll
+        for (int k = 0; k < C::R; ++k) out[k] = 0;
+        out[0] = row[zt[0]];
+        if constexpr (NW > 0) {
+            const uint32_t g = (uint32_t)A.gid[p];
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
+                uint32_t x[4];
+                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                const uint32_t rr = mulhi32(x[1], capw);
+                const uint2 e = tab[bin];
+                const int32_t t = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
+                out[C::rec_topic(k)] = t;
+                out[C::rec_topic(k) + 1] = row[t];
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
+        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+    }
+}
+
+// One piece = tokens [p0, p0 + n) that belong to words [w0, w1).
+template <int NW, int ND>
+__global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    __shared__ int32_t soff[kPieceWords + 1];
+    const int32_t pc_i = xcd_contiguous(A.n_pieces);
+    if (pc_i >= A.n_pieces) return;
+    const int4 pc = A.pieces[pc_i];  // (w0, w1, p0, n)
+    const int32_t nwords = pc.y - pc.x;
+    const int32_t K = A.K;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int32_t i = tid; i <= nwords; i += nt) soff[i] = A.woff[pc.x + i];
+    __syncthreads();
+    for (int32_t i = tid; i < pc.w; i += nt) {
+        const int32_t p = pc.z + i;
+        int32_t lo = 0, hi = nwords;  // soff[lo] <= p < soff[hi]
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (soff[mid] <= p) lo = mid; else hi = mid;
+        }
+        const int32_t w = pc.x + lo;
+        const size_t wk = (size_t)w * (size_t)K;
+        int32_t zt[C::S], out[C::R];
+        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+#pragma unroll
+        for (int k = 0; k < C::R; ++k) out[k] = 0;
+        out[0] = A.nkw[wk + (size_t)zt[0]];
+        if constexpr (NW > 0) {
+            const uint32_t g = (uint32_t)A.gid[p];
+            const uint32_t capw = A.cap[w];
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                uint32_t x[4];
+                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                const uint32_t rr = mulhi32(x[1], capw);
+                const uint4 e = A.alias[wk + bin];  // brings n_kw of both outcomes along
+                const bool keep = rr < e.x;
+                out[C::rec_topic(k)] = keep ? (int32_t)bin : (int32_t)e.y;
+                out[C::rec_topic(k) + 1] = keep ? (int32_t)e.z : (int32_t)e.w;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
+        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+    }
+}
+
+// ---- doc pass ------------------------------------------------------------------------
+
+struct TileDoc {  // document staged in an LDS tile
+    PackedDocTable tab;
+    const uint32_t* zs;  // the document's packed (topic | slot << 20) entries
+    int32_t L;
+    __device__ __forceinline__ int32_t count(int32_t k) const { return tab.count(k); }
+    __device__ __forceinline__ void token(uint32_t j, int32_t& topic, int32_t& nd) const
+    {
+        const uint32_t v = zs[j];
+        topic = (int32_t)(v & kTopicMask);
+        nd = tab.count_at(v >> kTopicBits);
+    }
+};
+
+struct LongDoc {  // document hashed in the global workspace
+    GlobalDocTable tab;
+    const int32_t* z;
+    int32_t L;
+    __device__ __forceinline__ int32_t count(int32_t k) const { return tab.count(k); }
+    __device__ __forceinline__ void token(uint32_t j, int32_t& topic, int32_t& nd) const
+    {
+        topic = z[j];
+        nd = tab.count(topic);
+    }
+};
+
+// The chains of T tokens of one thread, advanced together stage by stage.  doc[u] is
+// token u's document, own[u] its position in it, g[u] its CSR position (the Philox
+// counter), wp[u] its word-major position (where its word-pass record lies).
+template <int NW, int ND, int T, class DocView>
+__device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocView (&doc)[T],
+                                                const uint32_t (&own)[T], const uint32_t (&g)[T],
+                                                const int32_t (&wp)[T], int32_t (&s)[T])
+{
+#pragma clang fp contract(off)
+    using C = Chain<NW, ND>;
+    int32_t r[T][C::R];
+    int32_t z0[T], nds[T], nws[T], nks[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        doc[u].token(own[u], z0[u], nds[u]);
+        s[u] = z0[u];
+        nks[u] = A.nk[z0[u]];
+        nws[u] = r[u][0];
+    }
+#pragma unroll
+    for (int j = 0; j < C::M; ++j) {
+        const bool word_step = C::is_word(j);
+        const int i = C::index(j);
+        uint32_t x2[T];
+        int32_t t[T], ndt[T], nwt[T], nkt[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            uint32_t x[4];
+            philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+            x2[u] = x[2];
+            if (word_step) {
+                t[u] = r[u][C::rec_topic(i)];
+                nwt[u] = r[u][C::rec_topic(i) + 1];
+                ndt[u] = doc[u].count(t[u]);
+            } else {
+                const double u0 = unit_open(x[0]);
+                const double Ld = (double)doc[u].L;
+                if (u0 * (Ld + A.alphabar) < Ld) {
+                    doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[u], ndt[u]);
+                } else {
+                    t[u] = (int32_t)mulhi32(x[1], (uint32_t)A.K);
+                    ndt[u] = doc[u].count(t[u]);
+                }
+                nwt[u] = r[u][C::rec_doc(i)];
+            }
+            nkt[u] = A.nk[t[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
+            const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
+            // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
+            double num = (double)(ndt[u] - mt) + A.alpha;
+            num = num * ((double)(nwt[u] - mt) + A.beta);
+            num = num * ((double)(nks[u] - ms) + A.betabar);
+            double den = (double)(nds[u] - ms) + A.alpha;
+            den = den * ((double)(nws[u] - ms) + A.beta);
+            den = den * ((double)(nkt[u] - mt) + A.betabar);
+            if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
+                num = num * ((double)nws[u] + A.beta);
+                num = num * ((double)nkt[u] + A.betabar);
+                den = den * ((double)nwt[u] + A.beta);
+                den = den * ((double)nks[u] + A.betabar);
+            } else {          // Eq. (11): times p_d(s)/p_d(t)
+                num = num * ((double)nds[u] + A.alpha);
+                den = den * ((double)ndt[u] + A.alpha);
+            }
+            const double uu = unit_open(x2[u]);
+            const bool accept = (t[u] != s[u]) && (uu * den < num);
+            s[u] = accept ? t[u] : s[u];
+            nds[u] = accept ? ndt[u] : nds[u];
+            nws[u] = accept ? nwt[u] : nws[u];
+            nks[u] = accept ? nkt[u] : nks[u];
+        }
+    }
+}
+
+// T = tokens per thread; a tile has at most T * blockDim.x tokens.
+template <int NW, int ND, int T, int MAXB>
+__global__ __launch_bounds__(MAXB) void doc_pass_tiles_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    extern __shared__ int32_t smem[];
+    const int32_t c = xcd_contiguous(A.n_chunks);
+    if (c >= A.n_chunks) return;
+    const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
+    const int32_t ntok = A.doff[d1] - A.doff[d0];
+    if (ntok > A.cap_tokens || ntok == 0) return;  // a long document (other kernel) / nothing
+    const DocTile tile = load_doc_tile(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
+    TileDoc doc[T];
+    uint32_t own[T], g[T];
+    int32_t wp[T], s[T], idx[T];
+    bool live[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        // lanes past the end of the tile redo its last token and drop the result
+        int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+        live[u] = i < tile.ntok;
+        if (!live[u]) i = tile.ntok - 1;
+        idx[u] = i;
+        g[u] = (uint32_t)(tile.tok0 + i);
+        const int32_t dl = (int32_t)A.tokdoc[g[u]];
+        const int32_t b = tile.sdoff[dl];
+        doc[u].L = tile.sdoff[dl + 1] - b;
+        doc[u].tab = tile.table(dl);
+        doc[u].zs = tile.zs + b;
+        own[u] = (uint32_t)(i - b);
+        wp[u] = A.wpos[g[u]];
+    }
+    doc_pass_chains<NW, ND, T>(A, doc, own, g, wp, s);
+#pragma unroll
+    for (int u = 0; u < T; ++u)
+        if (live[u]) A.znew[g[u]] = s[u];
+    // the tile's new assignment replaces the staged snapshot; from it, the doc proposals
+    // of the next sweep
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u)
+        if (live[u]) tile.zs[idx[u]] = (uint32_t)s[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (!live[u]) continue;
+        int32_t row[C::S];
+#pragma unroll
+        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        row[0] = s[u];
+#pragma unroll
+        for (int k = 0; k < ND; ++k) {
+            uint32_t x[4];
+            philox4x32_10(g[u], 0u, A.sweep + 1u, (uint32_t)C::doc_step(k), A.seed_lo, A.seed_hi, x);
+            const uint32_t* zs = doc[u].zs;
+            row[1 + k] = doc_proposal(x[0], x[1], doc[u].L, A.K, A.alphabar,
+                                      [&](uint32_t j) { return (int32_t)zs[j]; });
+        }
+        store_ints<C::S>(A.zt + ((size_t)wp[u] << C::zt_shift), row);
+    }
+}
+
+template <int NW, int ND>
+__global__ __launch_bounds__(1024) void doc_pass_long_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    constexpr int T = 2;
+    const int32_t d = A.long_doc[blockIdx.x];
+    const int32_t tok0 = A.doff[d];
+    const int32_t Ld = A.doff[d + 1] - tok0;
+    const int64_t s0 = A.long_slot[blockIdx.x];
+    const GlobalDocTable table = load_long_doc(A.long_keys + s0, A.long_cnts + s0, A.z + tok0, Ld);
+    for (int32_t base = 0; base < Ld; base += T * (int32_t)blockDim.x) {
+        LongDoc doc[T];
+        uint32_t own[T], g[T];
+        int32_t wp[T], s[T];
+        bool live[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) {
+            int32_t i = base + (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+            live[u] = i < Ld;
+            if (!live[u]) i = Ld - 1;
+            doc[u].tab = table;
+            doc[u].z = A.z + tok0;
+            doc[u].L = Ld;
+            own[u] = (uint32_t)i;
+            g[u] = (uint32_t)(tok0 + i);
+            wp[u] = A.wpos[g[u]];
+        }
+        doc_pass_chains<NW, ND, T>(A, doc, own, g, wp, s);
+#pragma unroll
+        for (int u = 0; u < T; ++u)
+            if (live[u])
+                __hip_atomic_store(&A.znew[g[u]], s[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();  // the document's new assignment is complete
+    for (int32_t i = threadIdx.x; i < Ld; i += blockDim.x) {
+        const uint32_t g = (uint32_t)(tok0 + i);
+        int32_t row[C::S];
+#pragma unroll
+        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        row[0] = __hip_atomic_load(&A.znew[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int k = 0; k < ND; ++k) {
+            uint32_t x[4];
+            philox4x32_10(g, 0u, A.sweep + 1u, (uint32_t)C::doc_step(k), A.seed_lo, A.seed_hi, x);
+            row[1 + k] = doc_proposal(x[0], x[1], Ld, A.K, A.alphabar, [&](uint32_t j) {
+                return __hip_atomic_load(&A.znew[tok0 + (int32_t)j], __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+            });
+        }
+        store_ints<C::S>(A.zt + ((size_t)A.wpos[g] << C::zt_shift), row);
+    }
+}
+
+// ---- launch --------------------------------------------------------------------------
+
+template <class Kern>
+int raise_lds_limit(lda_ctx* c, Kern kern, size_t lds)
+{
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    return LDA_OK;
+}
+
+template <int NW, int ND, int T>
+int launch_doc_tiles(lda_ctx* c, const SplitArgs& A, size_t lds)
+{
+    int rc;
+    if (c->sweep_block <= 256) {
+        auto kern = doc_pass_tiles_kernel<NW, ND, T, 256>;
+        if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
+        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_chunks)), dim3(c->sweep_block), lds, c->stream, A);
+    } else {
+        auto kern = doc_pass_tiles_kernel<NW, ND, T, 1024>;
+        if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
+        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_chunks)), dim3(c->sweep_block), lds, c->stream, A);
+    }
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
+
+int tokens_per_thread(const lda_ctx* c)
+{
+    return (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
+}
+
+template <int NW, int ND>
+int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
+{
+    int rc;
+    if (need_proposals) {
+        hipLaunchKernelGGL((doc_proposals_kernel<NW, ND>), dim3(xcd_grid(c->n_chunks)), dim3(256), 0,
+                           c->stream, A);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_row_items > 0) {
+        auto kern = word_pass_rows_kernel<NW, ND>;
+        const size_t lds = sizeof(int32_t) * 3 * (size_t)c->K;
+        if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
+        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_row_items)), dim3(1024), lds, c->stream, A);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_gather_pieces > 0) {
+        hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND>), dim3(xcd_grid(c->n_gather_pieces)),
+                           dim3(256), 0, c->stream, A);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_chunks > 0) {
+        const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
+        const int tpt = tokens_per_thread(c);
+        rc = tpt <= 1 ? launch_doc_tiles<NW, ND, 1>(c, A, lds)
+           : tpt <= 2 ? launch_doc_tiles<NW, ND, 2>(c, A, lds)
+                      : launch_doc_tiles<NW, ND, 4>(c, A, lds);
+        if (rc != LDA_OK) return rc;
+    }
+    if (c->n_long > 0) {
+        hipLaunchKernelGGL((doc_pass_long_kernel<NW, ND>), dim3(c->n_long), dim3(1024), 0, c->stream,
+                           A);
+        LDA_HIP(c, hipGetLastError());
+    }
+    return LDA_OK;
+}
+
+// word and doc steps of a chain of mh_steps steps under proposal mode `mode`
+void chain_shape(int32_t mode, int32_t mh_steps, int32_t& nw, int32_t& nd)
+{
+    if (mode == 1) { nw = mh_steps; nd = 0; }
+    else if (mode == 2) { nw = 0; nd = mh_steps; }
+    else { nw = (mh_steps + 1) / 2; nd = mh_steps / 2; }
+}
+
+template <class T>
+int grow(lda_ctx* c, T** p, size_t* have, size_t need, const char* what)
+{
+    if (*have >= need) return LDA_OK;
+    if (*p) (void)hipFree(*p);
+    *p = nullptr;
+    *have = 0;
+    const hipError_t e = hipMalloc(reinterpret_cast<void**>(p), sizeof(T) * need);
+    if (e != hipSuccess) {
+        *p = nullptr;
+        (void)hipGetLastError();
+        return fail(c, LDA_ERR_OOM, "device allocation of %zu bytes for %s failed: %s",
+                    sizeof(T) * need, what, hipGetErrorString(e));
+    }
+    *have = need;
+    return LDA_OK;
+}
+
+}  // namespace
+
+// Chains of 1..4 steps in the cycle mode (and the one-step word chain), all-dense store,
+// tiles of at most 4 tokens per thread; everything else runs the fused kernel.
+bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps)
+{
+    if (c->hybrid || mh_steps < 1 || mh_steps > 4) return false;
+    if (c->opt.proposal_mode == 2 || (c->opt.proposal_mode == 1 && mh_steps != 1)) return false;
+    return tokens_per_thread(c) <= 4;
+}
+
+// Work lists of the word pass from the word segment offsets.
+int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
+{
+    std::vector<int4> items, pieces;
+    const int32_t V = c->V;
+    int32_t w0 = -1;  // first word of the open piece
+    auto close_piece = [&](int32_t w_end) {
+        if (w0 >= 0 && woff[w_end] > woff[w0])
+            pieces.push_back(make_int4(w0, w_end, woff[w0], woff[w_end] - woff[w0]));
+        w0 = -1;
+    };
+    for (int32_t w = 0; w < V; ++w) {
+        const int32_t b = woff[w], n = woff[w + 1] - b;
+        if (n >= kRowMinTokens) {
+            close_piece(w);
+            for (int32_t p = b; p < b + n; p += kRowItemTokens)
+                items.push_back(make_int4(w, p, std::min(kRowItemTokens, b + n - p), 0));
+            continue;
+        }
+        if (w0 >= 0 && (woff[w + 1] - woff[w0] > kPieceTokens || w + 1 - w0 > kPieceWords))
+            close_piece(w);
+        if (w0 < 0) w0 = w;
+    }
+    close_piece(V);
+    c->n_row_items = (int32_t)items.size();
+    c->n_gather_pieces = (int32_t)pieces.size();
+    if (!items.empty()) {
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_row_items), sizeof(int4) * items.size()));
+        LDA_HIP(c, hipMemcpy(c->d_row_items, items.data(), sizeof(int4) * items.size(),
+                             hipMemcpyHostToDevice));
+    }
+    if (!pieces.empty()) {
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_gather_pieces),
+                             sizeof(int4) * pieces.size()));
+        LDA_HIP(c, hipMemcpy(c->d_gather_pieces, pieces.data(), sizeof(int4) * pieces.size(),
+                             hipMemcpyHostToDevice));
+    }
+    return LDA_OK;
+}
+
+int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
+{
+    int32_t nw, nd;
+    chain_shape(c->opt.proposal_mode, mh_steps, nw, nd);
+    const int zt_shift = pow2_shift(1 + nd), rec_shift = pow2_shift(1 + 2 * nw + nd);
+    int rc;
+    if (c->zt_shift != zt_shift || c->zt_ints < ((size_t)c->N << zt_shift)) {
+        c->zt_current = false;
+        c->td_valid = false;
+        if ((rc = grow(c, &c->d_zt, &c->zt_ints, (size_t)c->N << zt_shift, "word-major records")) != LDA_OK)
+            return rc;
+        c->zt_shift = zt_shift;
+    }
+    if ((rc = grow(c, &c->d_rec, &c->rec_ints, (size_t)c->N << rec_shift, "word-pass records")) != LDA_OK)
+        return rc;
+    const bool have = c->zt_current &&
+                      (nd == 0 || (c->td_valid && c->td_sweep == c->sweep_index && c->td_nw == nw &&
+                                   c->td_nd == nd));
+    SplitArgs A{};
+    A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff; A.chunk_doc = c->d_chunk_doc;
+    A.tokdoc = c->d_tokdoc; A.wpos = c->d_wpos; A.gid = c->d_gid; A.woff = c->d_woff;
+    A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias; A.cap = c->d_cap;
+    A.zt = c->d_zt; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
+    A.n_chunks = c->n_chunks; A.n_row_items = c->n_row_items; A.n_pieces = c->n_gather_pieces;
+    A.K = c->K; A.cap_tokens = c->chunk_tokens;
+    A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
+    A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
+    A.long_doc = c->d_long_doc; A.long_slot = c->d_long_slot;
+    A.long_keys = c->d_long_keys; A.long_cnts = c->d_long_cnts;
+    // from here on the records are being rewritten: valid again only if every launch succeeds
+    c->zt_current = false;
+    c->td_valid = false;
+    if (nw == 1 && nd == 0) rc = launch_chain<1, 0>(c, A, !have);
+    else if (nw == 1 && nd == 1) rc = launch_chain<1, 1>(c, A, !have);
+    else if (nw == 2 && nd == 1) rc = launch_chain<2, 1>(c, A, !have);
+    else if (nw == 2 && nd == 2) rc = launch_chain<2, 2>(c, A, !have);
+    else rc = fail(c, LDA_ERR_UNSUPPORTED, "two-pass sweep: chain of %d word and %d doc steps", nw, nd);
+    if (rc != LDA_OK) return rc;
+    // the doc pass left (new z, doc proposals of the next sweep) in the records
+    c->zt_current = true;
+    c->td_valid = true;
+    c->td_sweep = c->sweep_index + 1u;
+    c->td_nw = nw;
+    c->td_nd = nd;
+    return LDA_OK;
+}
+
+}  // namespace lda
