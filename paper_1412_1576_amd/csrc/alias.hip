@@ -336,7 +336,7 @@ int launch_alias_build_hybrid(lda_ctx* c)
         DenseArgs a{};
         a.words = c->d_dense_alias_words; a.n_words = c->n_dense_alias; a.nkw = c->d_nkw;
         a.nk = c->d_nk; a.K = K; a.beta = c->beta; a.betabar = c->betabar; a.alias = c->d_alias;
-        a.cap = nullptr; a.metaA = c->d_metaA;
+        a.cap = c->d_cap; a.metaA = c->d_metaA;
         if (K <= lds_max) {
             size_t lds;
             lds_plan((size_t)K, lds, a.use_cache);

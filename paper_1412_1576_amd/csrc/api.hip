@@ -400,9 +400,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (hybrid) {
         TRY(setup_hybrid(c, woff));
         any_dense_alias = c->n_dense_alias > 0;
-    } else {
-        TRY(setup_split_sweep(c, woff));
     }
+    TRY(setup_split_sweep(c, woff));
     TRY(dev_alloc(c, &c->d_alias, any_dense_alias ? VK : 1, "alias tables"));
     std::vector<RebuildTile> tiles;
     std::vector<int32_t> multi;
@@ -431,7 +430,6 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY_HIP(hipStreamSynchronize(c->stream));
 #undef TRY
 #undef TRY_HIP
-    if (hybrid) dev_free(c->d_gid);  // only the two-pass sweep walks the word-major order
     c->state = COUNTS_VALID;
     c->sweep_index = 0;
     *out = c;

@@ -10,6 +10,7 @@
 // word step costs one gather for the draw and the proposed topic's n_kw together.
 #include "common.hpp"
 #include "doc_tile.hpp"
+#include "word_side.hpp"
 
 namespace lda {
 
@@ -174,55 +175,7 @@ __device__ __forceinline__ void mh_chains(const SweepArgs& A, const DocView (&do
     }
 }
 
-// ---- hybrid store: the word side of a token ------------------------------------------
-// STORE: 0 = every word has a dense row and a dense table (mh_chains above);
-// 1 = dense rows only, some words draw from the mixture; 2 = sparse rows as well.
-struct WordSide {
-    const uint4* tab;  // the word's own table: K dense bins, or its mixture bins
-    const void* row;   // dense n_kw row (int32[K]), or hash row (uint2[2^lg]) in store 2
-    uint32_t n, C;     // bins and capacity of the own table
-    uint32_t kind;     // bit 0: dense n_kw row, bit 1: dense proposal table
-    uint32_t lg;
-    uint64_t QS;       // integer mass of the sparse term (mixture form)
-};
-
-template <int STORE>
-__device__ __forceinline__ WordSide load_word(const SweepArgs& A, int32_t w)
-{
-    const uint4 a = A.metaA[2 * (size_t)w], b = A.metaB[2 * (size_t)w];  // one 32-byte record
-    WordSide v;
-    v.kind = b.w;
-    v.lg = b.z;
-    v.C = a.y;
-    v.QS = ((uint64_t)a.w << 32) | a.z;
-    const size_t wk = (size_t)w * (size_t)A.K;
-    const bool dense_tab = (b.w & 2u) != 0;
-    v.n = dense_tab ? (uint32_t)A.K : a.x;
-    v.tab = dense_tab ? A.alias + wk : A.ma + b.x;
-    if (STORE == 2 && !(b.w & 1u))
-        v.row = A.hs + b.y;
-    else
-        v.row = A.nkw + wk;
-    return v;
-}
-
-// n_kw[w][t]: dense row, or the word's hash row (Sec. 5)
-template <int STORE>
-__device__ __forceinline__ int32_t nkw_lookup(const WordSide& v, int32_t t)
-{
-    if (STORE != 2 || (v.kind & 1u)) return static_cast<const int32_t*>(v.row)[t];
-    const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
-    const uint32_t mask = (1u << v.lg) - 1u;
-    uint32_t s = row_hash_slot(t, v.lg);
-    for (uint32_t i = 0; i <= mask; ++i) {
-        const uint2 e = row[s];
-        if (e.x == (uint32_t)t) return (int32_t)e.y;
-        if (e.x == 0xFFFFFFFFu) return 0;
-        s = (s + 1) & mask;
-    }
-    return 0;
-}
-
+// ---- hybrid store -----------------------------------------------------------------------
 // Chains with the hybrid word side: dense tables for the head words, the
 // sparsified mixture (Sec. 4.2) for the others.  Same structure as mh_chains.
 // The three forms of a word step (dense table, sparse term, shared beta term)
@@ -235,9 +188,7 @@ __device__ __forceinline__ void mh_chains_hybrid(const SweepArgs& A, const DocVi
 {
 #pragma clang fp contract(off)
     const uint32_t K = (uint32_t)A.K;
-    const uint64_t QB = A.beta_hdr[0];
-    const uint32_t Cb = (uint32_t)A.beta_hdr[1];
-    const uint4* __restrict__ beta_pairs = reinterpret_cast<const uint4*>(A.beta_alias);
+    const BetaTable bt = load_beta_table(A);
     WordSide wv[T];
     int32_t z0[T], nds[T], nws[T], nks[T];
 #pragma unroll
@@ -256,38 +207,24 @@ __device__ __forceinline__ void mh_chains_hybrid(const SweepArgs& A, const DocVi
         uint32_t x2[T];
         int32_t t[T], ndt[T], nwt[T], nkt[T];
         if (word_step) {
-            uint32_t bin[T], rr[T], form[T];  // 0 dense table, 1 sparse term, 2 beta term
+            WordDraw d[T];
             uint4 e[T];
+            bool known[T];
 #pragma unroll
             for (int u = 0; u < T; ++u) {
                 uint32_t x[4];
                 philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
                 x2[u] = x[2];
-                // mixture: pick the term by its integer mass, then draw from that term's table
-                const double u3 = unit_open(x[3]);
-                const bool sparse_term = u3 * (double)(wv[u].QS + QB) < (double)wv[u].QS;
-                form[u] = (wv[u].kind & 2u) ? 0u : (sparse_term ? 1u : 2u);
-                const bool beta_term = form[u] == 2u;
-                bin[u] = mulhi32(x[0], beta_term ? K : wv[u].n);
-                rr[u] = mulhi32(x[1], beta_term ? Cb : wv[u].C);
-                const uint4* p = beta_term ? beta_pairs + (bin[u] >> 1) : wv[u].tab + bin[u];
-                e[u] = *p;
+                e[u] = *word_draw_address(wv[u], bt, K, x[0], x[1], x[3], d[u]);
             }
 #pragma unroll
             for (int u = 0; u < T; ++u) {
-                // beta table: two 8-byte bins per record
-                const bool odd = (form[u] == 2u) && (bin[u] & 1u);
-                const bool keep = rr[u] < (odd ? e[u].z : e[u].x);
-                int32_t tm, nm;
-                unpack_mix_bin(e[u], keep, tm, nm);
-                const int32_t td = keep ? (int32_t)bin[u] : (int32_t)(odd ? e[u].w : e[u].y);
-                t[u] = (form[u] == 1u) ? tm : td;
-                nwt[u] = (form[u] == 1u) ? nm : (keep ? (int32_t)e[u].z : (int32_t)e[u].w);
+                known[u] = word_draw_decode(d[u], e[u], t[u], nwt[u]);
                 nkt[u] = A.nk[t[u]];
             }
 #pragma unroll
             for (int u = 0; u < T; ++u) {
-                if (form[u] == 2u) nwt[u] = nkw_lookup<STORE>(wv[u], t[u]);
+                if (!known[u]) nwt[u] = nkw_lookup<STORE>(wv[u], t[u]);
                 ndt[u] = doc[u].count(t[u]);
             }
         } else {

@@ -27,6 +27,7 @@
 
 #include "common.hpp"
 #include "doc_tile.hpp"
+#include "word_side.hpp"
 
 namespace lda {
 
@@ -120,6 +121,13 @@ struct SplitArgs {
     int32_t K, cap_tokens;
     double alpha, beta, alphabar, betabar;
     uint32_t seed_lo, seed_hi, sweep;
+    // hybrid store / mixture proposal (null in the all-dense mode)
+    const uint4* metaA;
+    const uint4* metaB;
+    const uint4* ma;
+    const uint2* hs;
+    const uint2* beta_alias;
+    const uint64_t* beta_hdr;
     const int32_t* long_doc;
     const int64_t* long_slot;
     int32_t* long_keys;
@@ -235,8 +243,9 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     }
 }
 
-// One piece = tokens [p0, p0 + n) that belong to words [w0, w1).
-template <int NW, int ND>
+// One piece = tokens [p0, p0 + n) that belong to words [w0, w1).  STORE 0: every word
+// has a dense row and a dense table; 1, 2: hybrid store (word_side.hpp).
+template <int NW, int ND, int STORE>
 __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
 {
     using C = Chain<NW, ND>;
@@ -249,6 +258,8 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int32_t i = tid; i <= nwords; i += nt) soff[i] = A.woff[pc.x + i];
     __syncthreads();
+    BetaTable bt{};
+    if constexpr (STORE != 0 && NW > 0) bt = load_beta_table(A);
     for (int32_t i = tid; i < pc.w; i += nt) {
         const int32_t p = pc.z + i;
         int32_t lo = 0, hi = nwords;  // soff[lo] <= p < soff[hi]
@@ -257,29 +268,50 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
             if (soff[mid] <= p) lo = mid; else hi = mid;
         }
         const int32_t w = pc.x + lo;
-        const size_t wk = (size_t)w * (size_t)K;
         int32_t zt[C::S], out[C::R];
         load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
 #pragma unroll
         for (int k = 0; k < C::R; ++k) out[k] = 0;
-        out[0] = A.nkw[wk + (size_t)zt[0]];
-        if constexpr (NW > 0) {
-            const uint32_t g = (uint32_t)A.gid[p];
-            const uint32_t capw = A.cap[w];
+        if constexpr (STORE == 0) {
+            const size_t wk = (size_t)w * (size_t)K;
+            out[0] = A.nkw[wk + (size_t)zt[0]];
+            if constexpr (NW > 0) {
+                const uint32_t g = (uint32_t)A.gid[p];
+                const uint32_t capw = A.cap[w];
 #pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                uint32_t x[4];
-                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-                const uint32_t rr = mulhi32(x[1], capw);
-                const uint4 e = A.alias[wk + bin];  // brings n_kw of both outcomes along
-                const bool keep = rr < e.x;
-                out[C::rec_topic(k)] = keep ? (int32_t)bin : (int32_t)e.y;
-                out[C::rec_topic(k) + 1] = keep ? (int32_t)e.z : (int32_t)e.w;
+                for (int k = 0; k < NW; ++k) {
+                    uint32_t x[4];
+                    philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                    const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                    const uint32_t rr = mulhi32(x[1], capw);
+                    const uint4 e = A.alias[wk + bin];  // brings n_kw of both outcomes along
+                    const bool keep = rr < e.x;
+                    out[C::rec_topic(k)] = keep ? (int32_t)bin : (int32_t)e.y;
+                    out[C::rec_topic(k) + 1] = keep ? (int32_t)e.z : (int32_t)e.w;
+                }
             }
-        }
 #pragma unroll
-        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
+            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
+        } else {
+            const WordSide wv = load_word<STORE>(A, w);
+            out[0] = nkw_lookup<STORE>(wv, zt[0]);
+            if constexpr (NW > 0) {
+                const uint32_t g = (uint32_t)A.gid[p];
+#pragma unroll
+                for (int k = 0; k < NW; ++k) {
+                    uint32_t x[4];
+                    philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                    WordDraw d;
+                    const uint4 e = *word_draw_address(wv, bt, (uint32_t)K, x[0], x[1], x[3], d);
+                    int32_t t, nwt;
+                    if (!word_draw_decode(d, e, t, nwt)) nwt = nkw_lookup<STORE>(wv, t);
+                    out[C::rec_topic(k)] = t;
+                    out[C::rec_topic(k) + 1] = nwt;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = nkw_lookup<STORE>(wv, zt[1 + k]);
+        }
         store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
     }
 }
@@ -555,8 +587,13 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
         LDA_HIP(c, hipGetLastError());
     }
     if (c->n_gather_pieces > 0) {
-        hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND>), dim3(xcd_grid(c->n_gather_pieces)),
-                           dim3(256), 0, c->stream, A);
+        const dim3 grid(xcd_grid(c->n_gather_pieces));
+        if (!c->hybrid)
+            hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND, 0>), grid, dim3(256), 0, c->stream, A);
+        else if (c->H == c->V)
+            hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND, 1>), grid, dim3(256), 0, c->stream, A);
+        else
+            hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND, 2>), grid, dim3(256), 0, c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
     if (c->n_chunks > 0) {
@@ -603,11 +640,11 @@ int grow(lda_ctx* c, T** p, size_t* have, size_t need, const char* what)
 
 }  // namespace
 
-// Chains of 1..4 steps in the cycle mode (and the one-step word chain), all-dense store,
-// tiles of at most 4 tokens per thread; everything else runs the fused kernel.
+// Chains of 1..4 steps in the cycle mode (and the one-step word chain), tiles of at most
+// 4 tokens per thread; everything else runs the fused kernel.
 bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps)
 {
-    if (c->hybrid || mh_steps < 1 || mh_steps > 4) return false;
+    if (mh_steps < 1 || mh_steps > 4) return false;
     if (c->opt.proposal_mode == 2 || (c->opt.proposal_mode == 1 && mh_steps != 1)) return false;
     return tokens_per_thread(c) <= 4;
 }
@@ -623,12 +660,22 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
             pieces.push_back(make_int4(w0, w_end, woff[w0], woff[w_end] - woff[w0]));
         w0 = -1;
     };
+    // rows are staged for frequent words with a dense row and a dense table of at most
+    // max_alias_topics() bins (12 bytes of LDS per topic)
+    const bool rows_fit = c->K <= max_alias_topics();
     for (int32_t w = 0; w < V; ++w) {
         const int32_t b = woff[w], n = woff[w + 1] - b;
-        if (n >= kRowMinTokens) {
+        const bool dense_dense = !c->hybrid || c->h_wkind[w] == 3;
+        if (n >= kRowMinTokens && rows_fit && dense_dense) {
             close_piece(w);
             for (int32_t p = b; p < b + n; p += kRowItemTokens)
                 items.push_back(make_int4(w, p, std::min(kRowItemTokens, b + n - p), 0));
+            continue;
+        }
+        if (n > kPieceTokens) {  // a long word that cannot be staged: pieces of its own
+            close_piece(w);
+            for (int32_t p = b; p < b + n; p += kPieceTokens)
+                pieces.push_back(make_int4(w, w + 1, p, std::min(kPieceTokens, b + n - p)));
             continue;
         }
         if (w0 >= 0 && (woff[w + 1] - woff[w0] > kPieceTokens || w + 1 - w0 > kPieceWords))
@@ -679,6 +726,8 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
     A.K = c->K; A.cap_tokens = c->chunk_tokens;
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
     A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
+    A.metaA = c->d_metaA; A.metaB = c->d_metaB; A.ma = c->d_ma; A.hs = c->d_hs;
+    A.beta_alias = c->d_beta_alias; A.beta_hdr = c->d_beta_hdr;
     A.long_doc = c->d_long_doc; A.long_slot = c->d_long_slot;
     A.long_keys = c->d_long_keys; A.long_cnts = c->d_long_cnts;
     // from here on the records are being rewritten: valid again only if every launch succeeds

@@ -1,0 +1,114 @@
+// The word side of a token under the hybrid store (LightLDA Sec. 4.2 and 5): where the
+// word's proposal table and n_kw row live, one n_kw lookup, and one word-proposal draw
+// from the dense table or from the sparsified mixture.  Shared by the fused sweep and
+// the word pass of the two-pass sweep.
+//
+// STORE: 1 = every word has a dense n_kw row, some draw from the mixture;
+//        2 = sparse (hash) rows as well.
+// Args is a kernel argument block with the members metaA, metaB, alias, ma, hs, nkw, K.
+#pragma once
+
+#include "common.hpp"
+
+namespace lda {
+
+struct WordSide {
+    const uint4* tab;  // the word's own table: K dense bins, or its mixture bins
+    const void* row;   // dense n_kw row (int32[K]), or hash row (uint2[2^lg]) in store 2
+    uint32_t n, C;     // bins and capacity of the own table
+    uint32_t kind;     // bit 0: dense n_kw row, bit 1: dense proposal table
+    uint32_t lg;
+    uint64_t QS;       // integer mass of the sparse term (mixture form)
+};
+
+template <int STORE, class Args>
+__device__ __forceinline__ WordSide load_word(const Args& A, int32_t w)
+{
+    const uint4 a = A.metaA[2 * (size_t)w], b = A.metaB[2 * (size_t)w];  // one 32-byte record
+    WordSide v;
+    v.kind = b.w;
+    v.lg = b.z;
+    v.C = a.y;
+    v.QS = ((uint64_t)a.w << 32) | a.z;
+    const size_t wk = (size_t)w * (size_t)A.K;
+    const bool dense_tab = (b.w & 2u) != 0;
+    v.n = dense_tab ? (uint32_t)A.K : a.x;
+    v.tab = dense_tab ? A.alias + wk : A.ma + b.x;
+    if (STORE == 2 && !(b.w & 1u))
+        v.row = A.hs + b.y;
+    else
+        v.row = A.nkw + wk;
+    return v;
+}
+
+// n_kw[w][t]: dense row, or the word's hash row (Sec. 5)
+template <int STORE>
+__device__ __forceinline__ int32_t nkw_lookup(const WordSide& v, int32_t t)
+{
+    if (STORE != 2 || (v.kind & 1u)) return static_cast<const int32_t*>(v.row)[t];
+    const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
+    const uint32_t mask = (1u << v.lg) - 1u;
+    uint32_t s = row_hash_slot(t, v.lg);
+    for (uint32_t i = 0; i <= mask; ++i) {
+        const uint2 e = row[s];
+        if (e.x == (uint32_t)t) return (int32_t)e.y;
+        if (e.x == 0xFFFFFFFFu) return 0;
+        s = (s + 1) & mask;
+    }
+    return 0;
+}
+
+// The shared table of the mixture's beta term: (split, alias) bins read as aligned pairs.
+struct BetaTable {
+    const uint4* pairs;
+    uint64_t QB;
+    uint32_t C;
+};
+
+template <class Args>
+__device__ __forceinline__ BetaTable load_beta_table(const Args& A)
+{
+    return BetaTable{reinterpret_cast<const uint4*>(A.beta_alias), A.beta_hdr[0],
+                     (uint32_t)A.beta_hdr[1]};
+}
+
+// A word-proposal draw in two halves, so that a caller can keep several gathers in
+// flight.  The three forms of a draw (dense table, sparse term, shared beta term)
+// differ only in the address of the one 16-byte record they gather and in how it is
+// decoded, so every lane issues the same load.
+struct WordDraw {
+    uint32_t bin, rr;
+    uint32_t form;  // 0 dense table, 1 sparse term, 2 beta term
+};
+
+// x0, x1: bin and height; x3 picks the mixture's term by its integer mass
+__device__ __forceinline__ const uint4* word_draw_address(const WordSide& wv, const BetaTable& bt,
+                                                          uint32_t K, uint32_t x0, uint32_t x1,
+                                                          uint32_t x3, WordDraw& d)
+{
+#pragma clang fp contract(off)
+    const double u3 = unit_open(x3);
+    const bool sparse_term = u3 * (double)(wv.QS + bt.QB) < (double)wv.QS;
+    d.form = (wv.kind & 2u) ? 0u : (sparse_term ? 1u : 2u);
+    const bool beta_term = d.form == 2u;
+    d.bin = mulhi32(x0, beta_term ? K : wv.n);
+    d.rr = mulhi32(x1, beta_term ? bt.C : wv.C);
+    return beta_term ? bt.pairs + (d.bin >> 1) : wv.tab + d.bin;
+}
+
+// The proposed topic; n_kw of it unless the draw came from the beta term (returns
+// false: the caller looks it up).
+__device__ __forceinline__ bool word_draw_decode(const WordDraw& d, const uint4& e, int32_t& t,
+                                                 int32_t& nwt)
+{
+    const bool odd = (d.form == 2u) && (d.bin & 1u);  // beta table: two 8-byte bins per record
+    const bool keep = d.rr < (odd ? e.z : e.x);
+    int32_t tm, nm;
+    unpack_mix_bin(e, keep, tm, nm);
+    const int32_t td = keep ? (int32_t)d.bin : (int32_t)(odd ? e.w : e.y);
+    t = (d.form == 1u) ? tm : td;
+    nwt = (d.form == 1u) ? nm : (keep ? (int32_t)e.z : (int32_t)e.w);
+    return d.form != 2u;
+}
+
+}  // namespace lda
