@@ -202,6 +202,37 @@ def test_state_machine_and_checkpoint(lda_mod, oracle_mod):
     g.close(); h.close()
 
 
+def test_chain_shape_changes_between_sweeps(lda_mod, oracle_mod):
+    """The two-pass sweep keeps the next sweep's doc proposals from the previous doc pass;
+    they must be redrawn when the number of steps changes, after lda_set_z (other
+    assignment, other sweep index), and after a sweep that ran the fused kernel (5 steps).
+    Hybrid store too.  Every sweep is compared with the oracle."""
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=400, K=64)
+    doff, words = corpus.make_corpus(cfg)
+    rng = np.random.default_rng(4)
+    cnt = np.bincount(words, minlength=cfg.V)
+    for opt in ({}, {"dense_rows": 60, "dense_alias_min_count": int(cnt[60:].max()) + 1}):
+        g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=7, **opt)
+        o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=7,
+                              dense_alias_min_count=opt.get("dense_alias_min_count", 0))
+        for it, m in enumerate((2, 2, 4, 1, 3, 5, 2, 2, 1, 4)):
+            if it == 4:  # jump to another assignment and sweep index
+                z = rng.integers(0, cfg.K, g.N).astype(np.int32)
+                for x in (g, o):
+                    x.set_z(z, 1000)
+                    x.rebuild_counts()
+            g.build_alias(); o.build_alias()
+            g.sweep(m); o.sweep(m)
+            if it == 7:  # a second rebuild of the same assignment changes nothing
+                g.rebuild_counts()
+            g.rebuild_counts(); o.rebuild_counts()
+            assert np.array_equal(g.get_z(), o.get_z()), (opt, it, m)
+            assert np.array_equal(g.get_nk(), o.get_nk()), (opt, it, m)
+            for w in (0, 1, 61, cfg.V - 1):
+                assert np.array_equal(g.get_nkw_row(w), o.get_nkw_row(w)), (opt, it, m, w)
+        g.close(); o.close()
+
+
 def test_proposal_ablation_qualitative(lda_mod):
     """The paper's ablation (Sec. 7, cycle vs doc-only vs word-only proposals): with few MH
     steps the word-proposal alone sparsifies the word-topic table (best word-likelihood, worst
