@@ -83,6 +83,15 @@ int upload(lda_ctx* c, T** dst, const std::vector<T>& v, const char* what)
     return LDA_OK;
 }
 
+// A mixture word with a dense row whose tokens fit one rebuild tile gets its list of
+// non-zeros from the workgroup that histograms the row; the others from a compaction
+// pass over the row (needs h_wcount, h_wkind).
+bool list_from_rebuild(const lda_ctx* c, int32_t w)
+{
+    return c->hybrid && c->h_wkind[w] == 1 && c->h_wcount[w] <= c->rebuild_tile_tokens &&
+           c->K <= max_rebuild_topics();
+}
+
 // Word classes, list / hash-row offsets, work lists and buffers of the hybrid store.
 // woff: host copy of the word segment offsets.
 int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
@@ -130,7 +139,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
             else if (cap <= lds_max) cl = 3;
             mixc[cl].push_back(w);
             if (dense_row) {
-                compact.push_back(w);
+                if (!list_from_rebuild(c, w)) compact.push_back(w);
             } else {
                 sparse.push_back(w);
                 uint32_t hcap = 2;
@@ -313,6 +322,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     // a thread carries at most 8 tokens of its tile
     c->sweep_block = std::max(c->sweep_block, ((c->chunk_tokens + 7) / 8 + 63) / 64 * 64);
     const int32_t tile_tokens = o.rebuild_tile_tokens > 0 ? o.rebuild_tile_tokens : 262144;
+    c->rebuild_tile_tokens = tile_tokens;
 
     int rc = LDA_OK;
     auto bail = [&](int code) {
@@ -409,7 +419,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     for (int32_t w = 0; w < H; ++w) {
         const int32_t b = woff[w], e = woff[w + 1];
         if (e - b <= tile_tokens) {
-            tiles.push_back(RebuildTile{w, b, e, 0});
+            tiles.push_back(RebuildTile{w, b, e, list_from_rebuild(c, w) ? 2 : 0});
         } else {
             multi.push_back(w);
             for (int32_t p = b; p < e; p += tile_tokens)

@@ -23,7 +23,8 @@ struct RebuildTile {
     int32_t w;
     int32_t p0;
     int32_t p1;
-    int32_t multi;  // 1: the word has several tiles (row pre-zeroed, merged by atomics)
+    int32_t multi;  // 1: the word has several tiles (row pre-zeroed, merged by atomics);
+                    // 2: single tile of a mixture word, whose list of non-zeros is written too
 };
 
 }  // namespace lda
@@ -87,6 +88,7 @@ struct lda_ctx {
     // rebuild tiling
     lda::RebuildTile* d_tiles = nullptr;
     int32_t n_tiles = 0;
+    int32_t rebuild_tile_tokens = 0;
     int32_t* d_multi_words = nullptr;  // words that own several tiles
     int32_t n_multi_words = 0;
     // hybrid store / mixture proposal (Sec. 4.2 and 5); all null in the all-dense mode

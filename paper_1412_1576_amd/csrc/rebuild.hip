@@ -49,9 +49,14 @@ __global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restr
 __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __restrict__ tiles,
                                                          const int32_t* __restrict__ zw,
                                                          int32_t sh, int32_t K, int32_t span,
-                                                         int32_t* __restrict__ nkw)
+                                                         int32_t* __restrict__ nkw,
+                                                         const uint32_t* __restrict__ sp_off,
+                                                         int32_t* __restrict__ sp_topic,
+                                                         int32_t* __restrict__ sp_count,
+                                                         int32_t* __restrict__ sp_nnz)
 {
     extern __shared__ int32_t hist[];
+    __shared__ uint32_t wcnt[16];
     const RebuildTile t = tiles[blockIdx.x];
     const int32_t k0 = (int32_t)blockIdx.y * span;
     const int32_t nk_r = ((k0 + span < K) ? k0 + span : K) - k0;
@@ -64,11 +69,46 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
     }
     __syncthreads();
     int32_t* __restrict__ row = nkw + (size_t)t.w * (size_t)K + (size_t)k0;
-    if (t.multi) {
+    if (t.multi == 1) {
         for (int32_t k = tid; k < nk_r; k += nt) {
             const int32_t v = hist[k];
             if (v) atomicAdd(&row[k], v);
         }
+    } else if (t.multi == 2) {
+        // the whole row is here (one tile, one topic range): write it and the list of its
+        // non-zero topics, ascending
+        const size_t off = sp_off[t.w];
+        const int lane = tid & 63, wv = tid >> 6, nw = nt >> 6;
+        // every wave owns a contiguous run of topics: count its non-zeros, then place them
+        const int32_t chunk = (((nk_r + nw - 1) / nw) + 63) & ~63;
+        const int32_t kb0 = wv * chunk;
+        const int32_t kb1 = (kb0 + chunk < nk_r) ? kb0 + chunk : nk_r;
+        uint32_t cnt = 0;
+        for (int32_t kb = kb0; kb < kb1; kb += 64) {
+            const int32_t k = kb + lane;
+            const int32_t v = (k < kb1) ? hist[k] : 0;
+            if (k < kb1) row[k] = v;
+            cnt += (uint32_t)__popcll(__ballot(v > 0));
+        }
+        if (lane == 0) wcnt[wv] = cnt;
+        __syncthreads();
+        uint32_t base = 0, pos = 0;
+        for (int i = 0; i < nw; ++i) {
+            if (i < wv) pos += wcnt[i];
+            base += wcnt[i];
+        }
+        for (int32_t kb = kb0; kb < kb1; kb += 64) {
+            const int32_t k = kb + lane;
+            const int32_t v = (k < kb1) ? hist[k] : 0;
+            const uint64_t mask = __ballot(v > 0);
+            if (v > 0) {
+                const size_t p = off + pos + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                sp_topic[p] = k;
+                sp_count[p] = v;
+            }
+            pos += (uint32_t)__popcll(mask);
+        }
+        if (tid == 0) sp_nnz[t.w] = (int32_t)base;
     } else {
         for (int32_t k = tid; k < nk_r; k += nt) row[k] = hist[k];
     }
@@ -144,7 +184,7 @@ int launch_dense_rows(lda_ctx* c)
     hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
                        dim3(span <= 512 ? 256 : 1024), lds, c->stream, c->d_tiles, c->d_zt,
                        c->zt_shift, K, span,
-                       c->d_nkw);
+                       c->d_nkw, c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }
