@@ -56,7 +56,7 @@ void free_all(lda_ctx* c)
 {
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
     dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
-    dev_free(c->d_row_items); dev_free(c->d_gather_pieces); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
+    dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
     dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);

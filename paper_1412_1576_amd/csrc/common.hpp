@@ -64,8 +64,9 @@ struct lda_ctx {
     // Work lists of the word pass: items (w, p0, n, 0) whose rows are staged in LDS, and
     // pieces (w0, w1, p0, n) of several short words whose rows are gathered
     int4* d_row_items = nullptr;
+    int4* d_mix_items = nullptr;  // items (w, p0, n, 0) of mixture words whose row is rebuilt in LDS
     int4* d_gather_pieces = nullptr;
-    int32_t n_row_items = 0, n_gather_pieces = 0;
+    int32_t n_row_items = 0, n_mix_items = 0, n_gather_pieces = 0;
     int32_t* d_woff = nullptr;  // [V+1] segment offsets
     // model
     int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)

@@ -30,8 +30,10 @@ __host__ __device__ inline size_t doc_tile_lds_bytes(int32_t cap_tokens, int32_t
 }
 
 // Stage documents [d0, d1) and build their tables.  tokdoc[g] is the index of
-// token g's document inside its tile (NULL: found by binary search).  All threads
-// of the block must call it; it ends with a barrier.
+// token g's document inside its tile (NULL: found by binary search).  STREAM: read z
+// and tokdoc with the non-temporal hint (a caller that wants its L2 for other data).
+// All threads of the block must call it; it ends with a barrier.
+template <bool STREAM = false>
 __device__ __forceinline__ DocTile load_doc_tile(int32_t* smem, int32_t cap_tokens,
                                                  const int32_t* __restrict__ z,
                                                  const int32_t* __restrict__ doff,
@@ -48,12 +50,14 @@ __device__ __forceinline__ DocTile load_doc_tile(int32_t* smem, int32_t cap_toke
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int32_t i = tid; i <= t.nd; i += nt) t.sdoff[i] = doff[d0 + i] - t.tok0;
     for (int32_t i = tid; i < t.ntok; i += nt) {
-        t.zs[i] = (uint32_t)z[t.tok0 + i];
+        t.zs[i] = (uint32_t)(STREAM ? __builtin_nontemporal_load(&z[t.tok0 + i]) : z[t.tok0 + i]);
         reinterpret_cast<uint2*>(t.tab)[i] = make_uint2(kEmptySlot, kEmptySlot);
     }
     __syncthreads();
     for (int32_t i = tid; i < t.ntok; i += nt) {
-        const int32_t dl = tokdoc ? (int32_t)tokdoc[t.tok0 + i] : find_doc(t.sdoff, t.nd, i);
+        const int32_t dl = tokdoc ? (int32_t)(STREAM ? __builtin_nontemporal_load(&tokdoc[t.tok0 + i])
+                                                     : tokdoc[t.tok0 + i])
+                                  : find_doc(t.sdoff, t.nd, i);
         const uint32_t zi = t.zs[i];
         t.zs[i] = zi | (t.table(dl).insert((int32_t)zi) << kTopicBits);  // own element only
     }

@@ -36,6 +36,8 @@ namespace {
 constexpr int kXcds = 8;
 constexpr int32_t kRowItemTokens = 16384;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
+constexpr int32_t kMixRowTopics = 16384;   // largest K whose n_kw row a mixture item keeps in LDS
+constexpr int32_t kMixRowMinTokens = 128;
 constexpr int32_t kPieceTokens = 4096;     // tokens of a gather piece
 constexpr int32_t kPieceWords = 4096;      // words of a gather piece (their offsets sit in LDS)
 
@@ -128,6 +130,12 @@ struct SplitArgs {
     const uint2* hs;
     const uint2* beta_alias;
     const uint64_t* beta_hdr;
+    const uint32_t* sp_off;
+    const int32_t* sp_topic;
+    const int32_t* sp_count;
+    const int32_t* sp_nnz;
+    const int4* mix_items;
+    int32_t n_mix_items;
     const int32_t* long_doc;
     const int64_t* long_slot;
     int32_t* long_keys;
@@ -316,6 +324,59 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
     }
 }
 
+// One item = up to kRowItemTokens consecutive tokens of one mixture word that has a dense
+// n_kw row.  The row is rebuilt in LDS from the word's list of non-zeros (8 bytes per
+// non-zero instead of 4 K bytes from memory), so every n_kw lookup is an LDS read; the
+// draw gathers one bin of the word's own table or of the shared beta table.
+template <int NW, int ND>
+__global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
+{
+    using C = Chain<NW, ND>;
+    extern __shared__ int32_t smem[];
+    int32_t* __restrict__ row = smem;  // [K] n_kw
+    const int32_t it_i = xcd_contiguous(A.n_mix_items);
+    if (it_i >= A.n_mix_items) return;
+    const int4 it = A.mix_items[it_i];  // (w, p0, n, 0)
+    const int32_t K = A.K, w = it.x;
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int32_t k = tid; k < K; k += nt) row[k] = 0;
+    __syncthreads();
+    {
+        const size_t off = A.sp_off[w];
+        const int32_t nnz = A.sp_nnz[w];
+        for (int32_t i = tid; i < nnz; i += nt) row[A.sp_topic[off + i]] = A.sp_count[off + i];
+    }
+    __syncthreads();
+    const WordSide wv = load_word<1>(A, w);
+    BetaTable bt{};
+    if constexpr (NW > 0) bt = load_beta_table(A);
+    for (int32_t i = tid; i < it.z; i += nt) {
+        const int32_t p = it.y + i;
+        int32_t zt[C::S], out[C::R];
+        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+#pragma unroll
+        for (int k = 0; k < C::R; ++k) out[k] = 0;
+        out[0] = row[zt[0]];
+        if constexpr (NW > 0) {
+            const uint32_t g = (uint32_t)A.gid[p];
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                uint32_t x[4];
+                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                WordDraw d;
+                const uint4 e = *word_draw_address(wv, bt, (uint32_t)K, x[0], x[1], x[3], d);
+                int32_t t, nwt;
+                if (!word_draw_decode(d, e, t, nwt)) nwt = row[t];
+                out[C::rec_topic(k)] = t;
+                out[C::rec_topic(k) + 1] = nwt;
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
+        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+    }
+}
+
 // ---- doc pass ------------------------------------------------------------------------
 
 struct TileDoc {  // document staged in an LDS tile
@@ -345,18 +406,16 @@ struct LongDoc {  // document hashed in the global workspace
 
 // The chains of T tokens of one thread, advanced together stage by stage.  doc[u] is
 // token u's document, own[u] its position in it, g[u] its CSR position (the Philox
-// counter), wp[u] its word-major position (where its word-pass record lies).
+// counter), r[u] its word-pass record.
 template <int NW, int ND, int T, class DocView>
 __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocView (&doc)[T],
                                                 const uint32_t (&own)[T], const uint32_t (&g)[T],
-                                                const int32_t (&wp)[T], int32_t (&s)[T])
+                                                const int32_t (&r)[T][Chain<NW, ND>::R],
+                                                int32_t (&s)[T])
 {
 #pragma clang fp contract(off)
     using C = Chain<NW, ND>;
-    int32_t r[T][C::R];
     int32_t z0[T], nds[T], nws[T], nks[T];
-#pragma unroll
-    for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         doc[u].token(own[u], z0[u], nds[u]);
@@ -423,6 +482,12 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
 }
 
 // T = tokens per thread; a tile has at most T * blockDim.x tokens.
+//
+// The token streams (z, document indices, word-major positions, the new z) are read and
+// written once, with the streaming hint: what should stay in L2 are the lines of
+// word-major records, which the tokens of a frequent word read (8 records a line) and
+// write (16 a line) one after the other -- every record line evicted before it is complete
+// costs a partial write to memory.
 template <int NW, int ND, int T, int MAXB>
 __global__ __launch_bounds__(MAXB) void doc_pass_tiles_kernel(SplitArgs A)
 {
@@ -433,31 +498,39 @@ __global__ __launch_bounds__(MAXB) void doc_pass_tiles_kernel(SplitArgs A)
     const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
     const int32_t ntok = A.doff[d1] - A.doff[d0];
     if (ntok > A.cap_tokens || ntok == 0) return;  // a long document (other kernel) / nothing
-    const DocTile tile = load_doc_tile(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
-    TileDoc doc[T];
+    // the word-pass records do not depend on the tile: their gather (one random line per
+    // token) is issued first and overlaps the staging of the documents
+    const int32_t tok0 = A.doff[d0];
     uint32_t own[T], g[T];
-    int32_t wp[T], s[T], idx[T];
+    int32_t wp[T], s[T], idx[T], r[T][C::R];
     bool live[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         // lanes past the end of the tile redo its last token and drop the result
         int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
-        live[u] = i < tile.ntok;
-        if (!live[u]) i = tile.ntok - 1;
+        live[u] = i < ntok;
+        if (!live[u]) i = ntok - 1;
         idx[u] = i;
-        g[u] = (uint32_t)(tile.tok0 + i);
-        const int32_t dl = (int32_t)A.tokdoc[g[u]];
+        g[u] = (uint32_t)(tok0 + i);
+        wp[u] = __builtin_nontemporal_load(&A.wpos[g[u]]);
+    }
+#pragma unroll
+    for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
+    const DocTile tile = load_doc_tile<true>(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
+    TileDoc doc[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        const int32_t dl = (int32_t)__builtin_nontemporal_load(&A.tokdoc[g[u]]);
         const int32_t b = tile.sdoff[dl];
         doc[u].L = tile.sdoff[dl + 1] - b;
         doc[u].tab = tile.table(dl);
         doc[u].zs = tile.zs + b;
-        own[u] = (uint32_t)(i - b);
-        wp[u] = A.wpos[g[u]];
+        own[u] = (uint32_t)(idx[u] - b);
     }
-    doc_pass_chains<NW, ND, T>(A, doc, own, g, wp, s);
+    doc_pass_chains<NW, ND, T>(A, doc, own, g, r, s);
 #pragma unroll
     for (int u = 0; u < T; ++u)
-        if (live[u]) A.znew[g[u]] = s[u];
+        if (live[u]) __builtin_nontemporal_store(s[u], &A.znew[g[u]]);
     // the tile's new assignment replaces the staged snapshot; from it, the doc proposals
     // of the next sweep
     __syncthreads();
@@ -511,7 +584,10 @@ __global__ __launch_bounds__(1024) void doc_pass_long_kernel(SplitArgs A)
             g[u] = (uint32_t)(tok0 + i);
             wp[u] = A.wpos[g[u]];
         }
-        doc_pass_chains<NW, ND, T>(A, doc, own, g, wp, s);
+        int32_t r[T][C::R];
+#pragma unroll
+        for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
+        doc_pass_chains<NW, ND, T>(A, doc, own, g, r, s);
 #pragma unroll
         for (int u = 0; u < T; ++u)
             if (live[u])
@@ -586,6 +662,13 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
         hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_row_items)), dim3(1024), lds, c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
+    if (c->n_mix_items > 0) {
+        auto kern = word_pass_mix_rows_kernel<NW, ND>;
+        const size_t lds = sizeof(int32_t) * (size_t)c->K;
+        if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
+        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_mix_items)), dim3(512), lds, c->stream, A);
+        LDA_HIP(c, hipGetLastError());
+    }
     if (c->n_gather_pieces > 0) {
         const dim3 grid(xcd_grid(c->n_gather_pieces));
         if (!c->hybrid)
@@ -652,7 +735,7 @@ bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps)
 // Work lists of the word pass from the word segment offsets.
 int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
 {
-    std::vector<int4> items, pieces;
+    std::vector<int4> items, mix_items, pieces;
     const int32_t V = c->V;
     int32_t w0 = -1;  // first word of the open piece
     auto close_piece = [&](int32_t w_end) {
@@ -672,6 +755,14 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
                 items.push_back(make_int4(w, p, std::min(kRowItemTokens, b + n - p), 0));
             continue;
         }
+        // a mixture word with a dense row of at most kMixRowTopics topics and enough
+        // tokens to pay for clearing an LDS row
+        if (c->hybrid && c->h_wkind[w] == 1 && c->K <= kMixRowTopics && n >= kMixRowMinTokens) {
+            close_piece(w);
+            for (int32_t p = b; p < b + n; p += kRowItemTokens)
+                mix_items.push_back(make_int4(w, p, std::min(kRowItemTokens, b + n - p), 0));
+            continue;
+        }
         if (n > kPieceTokens) {  // a long word that cannot be staged: pieces of its own
             close_piece(w);
             for (int32_t p = b; p < b + n; p += kPieceTokens)
@@ -684,6 +775,12 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
     }
     close_piece(V);
     c->n_row_items = (int32_t)items.size();
+    c->n_mix_items = (int32_t)mix_items.size();
+    if (!mix_items.empty()) {
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_mix_items), sizeof(int4) * mix_items.size()));
+        LDA_HIP(c, hipMemcpy(c->d_mix_items, mix_items.data(), sizeof(int4) * mix_items.size(),
+                             hipMemcpyHostToDevice));
+    }
     c->n_gather_pieces = (int32_t)pieces.size();
     if (!items.empty()) {
         LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_row_items), sizeof(int4) * items.size()));
@@ -728,6 +825,8 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
     A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
     A.metaA = c->d_metaA; A.metaB = c->d_metaB; A.ma = c->d_ma; A.hs = c->d_hs;
     A.beta_alias = c->d_beta_alias; A.beta_hdr = c->d_beta_hdr;
+    A.sp_off = c->d_sp_off; A.sp_topic = c->d_sp_topic; A.sp_count = c->d_sp_count;
+    A.sp_nnz = c->d_sp_nnz; A.mix_items = c->d_mix_items; A.n_mix_items = c->n_mix_items;
     A.long_doc = c->d_long_doc; A.long_slot = c->d_long_slot;
     A.long_keys = c->d_long_keys; A.long_cnts = c->d_long_cnts;
     // from here on the records are being rewritten: valid again only if every launch succeeds
