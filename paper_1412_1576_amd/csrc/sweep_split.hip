@@ -9,7 +9,7 @@
 //
 //   word pass  word-major.  Frequent words: a workgroup stages the word's n_kw row and
 //              its table in LDS and serves a run of the word's tokens from there
-//              (one coalesced read of the rows per 16384 tokens instead of three random
+//              (one coalesced read of the rows per 32768 tokens instead of three random
 //              128-byte lines per token).  Short words: the rows are gathered; the
 //              word's tokens are processed together, so its lines are reused in L2.
 //              Output: one record per token (n_kw at its snapshot topic, the proposed
@@ -34,7 +34,7 @@ namespace lda {
 namespace {
 
 constexpr int kXcds = 8;
-constexpr int32_t kRowItemTokens = 16384;  // tokens a workgroup serves from one staging of the rows
+constexpr int32_t kRowItemTokens = 32768;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
 constexpr int32_t kMixRowTopics = 16384;   // largest K whose n_kw row a mixture item keeps in LDS
 constexpr int32_t kMixRowMinTokens = 128;
@@ -488,8 +488,11 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
 // word-major records, which the tokens of a frequent word read (8 records a line) and
 // write (16 a line) one after the other -- every record line evicted before it is complete
 // costs a partial write to memory.
+// Up to two tokens per thread in 256-thread blocks (the default tiling) are compiled for
+// 7 waves per SIMD: one more resident workgroup per CU hides more of the gather latency
+// than the few registers it costs.
 template <int NW, int ND, int T, int MAXB>
-__global__ __launch_bounds__(MAXB) void doc_pass_tiles_kernel(SplitArgs A)
+__global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256) ? 7 : 1) void doc_pass_tiles_kernel(SplitArgs A)
 {
     using C = Chain<NW, ND>;
     extern __shared__ int32_t smem[];
