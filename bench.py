@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the MI355X LightLDA hot path: tokens/s of whole iterations
 (alias build + cycle-MH sweep + count rebuild) on a synthetic Zipf corpus,
-the sweep kernel's roofline figures, and the CPU oracle timed beside it.
+the roofline figures of the sweep's dominant kernel, and the CPU oracle timed beside it.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c1] [--mh-steps M]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c1|c4|c5] [--mh-steps M]
 
 Prints ONE JSON line.  One GPU only: --gpus N with N > 1 exits with a message.
 """
@@ -33,21 +33,27 @@ def algorithmic_bytes_per_token(mh_steps: int) -> float:
     return 40.0 + 22.0 * mh_steps
 
 
-def design_bytes_per_token(mh_steps: int) -> float:
-    """What this design has to bring from HBM per token: the stream (word id,
-    z in, z out: 12 B; the document side is then served from LDS), n_kw and n_k at
-    the snapshot topic (8 B), per word step an alias bin + n_kw + n_k (16 B), per
-    doc step n_kw + n_k (8 B)."""
-    word_steps = (mh_steps + 1) // 2
-    doc_steps = mh_steps // 2
-    return 12.0 + 8.0 + 16.0 * word_steps + 8.0 * doc_steps
+def chain_shape(mh_steps: int):
+    """(word steps, doc steps) of a cycle chain that starts with a word step."""
+    return (mh_steps + 1) // 2, mh_steps // 2
 
 
-# HBM-side bytes per sweep launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (profiles/all_kernels_c3_mh2.txt: counter KiB x calibration factor x 1024, fetched +
-# written); keyed by (workload, mh_steps).  None where not measured.
+def doc_pass_bytes_per_token(mh_steps: int) -> float:
+    """The doc pass's share of the figure above: token stream 16 B, document header 8 B,
+    n_k and the n_kd probe at the snapshot topic 12 B, per word step n_k + n_kd probe
+    12 B, per doc step z of a random token + n_k + n_kd probe 16 B (64 B for 2 steps).
+    The rest -- every n_kw and the alias bins, 4 + 12 per word step + 4 per doc step --
+    is the word pass's share."""
+    nw, nd = chain_shape(mh_steps)
+    return 36.0 + 12.0 * nw + 16.0 * nd
+
+
+# HBM-side bytes per launch of the doc pass kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this command (profiles/all_kernels_c3_mh2.txt: counter KiB x calibration factor x 1024,
+# fetched + written); keyed by (workload, mh_steps, dense_alias_min_count).  None where not
+# measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2): (112_957_986.2 * 2.000 + 3_040_537.5 * 1.000) * 1024.0,
+    ("c3", 2, 10000): (18_718_656.6 * 2.000 + 15_155_716.1 * 1.000) * 1024.0,
 }
 
 
@@ -91,8 +97,9 @@ def main():
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--dense-alias-min-count", type=int, default=-1, help="c1-c3: words with "
-                    "fewer tokens draw from the mixture word-proposal (Sec. 4.2) instead of a "
-                    "dense K-bin table; 0 = dense tables for every word")
+                    "fewer tokens draw from the sparsified mixture word-proposal (Sec. 4.2) "
+                    "instead of a dense K-bin table; -1 (default) = K; 0 = dense tables for "
+                    "every word")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); multi-GPU sharding is a "
@@ -127,18 +134,21 @@ def main():
             max(dense_rows, 0), hybrid["dense_alias_min_count"])
         del cnt, tail
         args.no_cpu_baseline = True  # the oracle keeps a dense V x K table
-    elif args.dense_alias_min_count > 0:
-        hybrid = dict(dense_rows=0, dense_alias_min_count=args.dense_alias_min_count)
-        store = "dense n_kw, mixture proposal below count %d" % args.dense_alias_min_count
+    elif args.dense_alias_min_count != 0:
+        min_count = cfg.K if args.dense_alias_min_count < 0 else args.dense_alias_min_count
+        hybrid = dict(dense_rows=0, dense_alias_min_count=min_count)
+        store = "dense n_kw, mixture proposal below count %d" % min_count
 
     stream = torch.cuda.Stream()
     t0 = time.perf_counter()
     g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                 stream=stream.cuda_stream, sweep_chunk_tokens=args.chunk_tokens,
                 sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens,
-                **hybrid)
+                time_sweep_passes=1, **hybrid)
     g.sync()
     t_init = time.perf_counter() - t0
+
+    pass_ms = []  # (word pass, doc pass kernel) of every timed sweep, from the library's events
 
     def iteration(evs=None):
         if evs:
@@ -152,6 +162,10 @@ def main():
         g.rebuild_counts()
         if evs:
             evs[3].record(stream)
+            try:
+                pass_ms.append(g.sweep_pass_ms())
+            except lda.LdaError:   # this chain shape runs as one fused kernel
+                pass
 
     for _ in range(args.warmup):
         iteration()
@@ -186,7 +200,14 @@ def main():
 
     ms_per_step = total_ms / args.steps
     abytes = algorithmic_bytes_per_token(args.mh_steps)
-    achieved = abytes * N / (sweep_ms * 1e-3) / 1e9
+    if len(pass_ms) == args.steps:
+        word_ms = sum(p[0] for p in pass_ms) / args.steps
+        doc_ms = sum(p[1] for p in pass_ms) / args.steps
+        dominant, dbytes = "doc_pass_tiles_kernel", doc_pass_bytes_per_token(args.mh_steps)
+    else:
+        word_ms, doc_ms = None, sweep_ms
+        dominant, dbytes = "sweep_tiles_kernel", abytes
+    achieved = dbytes * N / (doc_ms * 1e-3) / 1e9
     out = {
         "metric": "sampled tokens/sec (alias build + %d-step MH sweep + count rebuild)" % args.mh_steps,
         "value": N / (ms_per_step * 1e-3),
@@ -206,22 +227,25 @@ def main():
                                              cfg.alpha, cfg.beta, args.mh_steps, store),
             "sweep_tokens_per_s": N / (sweep_ms * 1e-3),
             "alias_ms": alias_ms, "sweep_ms": sweep_ms, "rebuild_ms": rebuild_ms,
+            "word_pass_ms": word_ms, "doc_pass_kernel_ms": doc_ms,
+            "sweep_algorithmic_bytes_per_token": abytes,
+            "sweep_achieved_GBs": abytes * N / (sweep_ms * 1e-3) / 1e9,
             "wall_s_timed_region": wall, "corpus_gen_s": t_gen, "init_s": t_init,
             "loglik_after": loglik,
         },
         "roofline": {
-            "bound": "hbm", "kernel": "sweep_tiles_kernel",
+            "bound": "hbm", "kernel": dominant,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "algorithmic_bytes_per_token": abytes,
-            "design_bytes_per_token": design_bytes_per_token(args.mh_steps),
+            "algorithmic_bytes_per_token": dbytes,
             "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name if not args.docs else None,
-                                                   args.mh_steps)),
+                                                   args.mh_steps,
+                                                   hybrid.get("dense_alias_min_count", 0))),
         },
     }
     g.close()
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 3000, "c3": 30000}[args.workload]
+        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 3000, "c3": 300000}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample,
                                            hybrid.get("dense_alias_min_count", 0))
     print(json.dumps(out))

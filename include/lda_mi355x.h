@@ -68,7 +68,9 @@ typedef struct lda_options {
     int32_t sweep_chunk_tokens;    /* tuning: tokens per sweep workgroup tile; 0: default */
     int32_t sweep_block_threads;   /* tuning: threads per sweep workgroup; 0: default */
     int32_t rebuild_tile_tokens;   /* tuning: tokens per count-rebuild tile; 0: default */
-    int32_t reserved[9];           /* must be zero */
+    int32_t time_sweep_passes;     /* 1: lda_sweep records HIP events around its two passes on the
+                                      context's stream (read them with lda_sweep_pass_ms) */
+    int32_t reserved[8];           /* must be zero */
 } lda_options;
 
 /*
@@ -107,6 +109,17 @@ int lda_build_alias(lda_ctx* ctx);
  * ALIAS_VALID -> SWEPT (the counts no longer match z).
  */
 int lda_sweep(lda_ctx* ctx, int32_t mh_steps);
+
+/*
+ * lda_sweep_pass_ms -- device time of the last sweep's two passes, from the HIP events
+ * recorded with the option time_sweep_passes: *word_pass_ms covers the word pass (every
+ * kernel that evaluates the word side of the chains, Eq. 6-8, in word-major order),
+ * *doc_pass_ms the one kernel that runs the accept tests over the document tiles.
+ * Waits for the events.  LDA_ERR_STATE if the option is off, no sweep has run, or the
+ * last sweep ran as one fused kernel (more than 4 steps, word-only or doc-only chains of
+ * several steps, tiles of more than 4 tokens per thread).
+ */
+int lda_sweep_pass_ms(lda_ctx* ctx, float* word_pass_ms, float* doc_pass_ms);
 
 /*
  * lda_rebuild_counts -- recount n_kw (per-word histogram of the word-major

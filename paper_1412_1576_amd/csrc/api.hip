@@ -56,7 +56,11 @@ void free_all(lda_ctx* c)
 {
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
     dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
-    dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces); dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
+    dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces);
+    for (hipEvent_t& e : c->pass_ev) {
+        if (e) (void)hipEventDestroy(e);
+        e = nullptr;
+    } dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
     dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
@@ -282,9 +286,10 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     if (o.proposal_mode < 0 || o.proposal_mode > 2)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: proposal_mode must be 0, 1 or 2");
     if (o.dense_rows < -1 || o.dense_alias_min_count < 0 || o.sweep_chunk_tokens < 0 ||
-        o.sweep_block_threads < 0 || o.rebuild_tile_tokens < 0)
-        return fail(nullptr, LDA_ERR_ARG, "lda_init: negative option");
-    for (int i = 0; i < 9; ++i)
+        o.sweep_block_threads < 0 || o.rebuild_tile_tokens < 0 || o.time_sweep_passes < 0 ||
+        o.time_sweep_passes > 1)
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
+    for (int i = 0; i < 8; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
     const bool hybrid = (o.dense_rows != 0) || (o.dense_alias_min_count != 0);
     const int32_t H = o.dense_rows < 0 ? 0 : (o.dense_rows == 0 ? V : std::min(o.dense_rows, V));
@@ -479,11 +484,24 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
         rc = c->hybrid ? launch_sweep_hybrid(c, mh_steps) : launch_sweep(c, mh_steps);
         c->zt_current = false;  // the fused kernels write the doc-major assignment only
         c->td_valid = false;
+        c->pass_ev_recorded = false;
     }
     if (rc != LDA_OK) return rc;
     std::swap(c->d_z, c->d_znew);
     c->sweep_index += 1;
     c->state = SWEPT;
+    return LDA_OK;
+}
+
+int lda_sweep_pass_ms(lda_ctx* c, float* word_pass_ms, float* doc_pass_ms)
+{
+    if (!c) return LDA_ERR_ARG;
+    if (!word_pass_ms || !doc_pass_ms) return fail(c, LDA_ERR_ARG, "lda_sweep_pass_ms: NULL pointer");
+    if (!c->opt.time_sweep_passes || !c->pass_ev_recorded)
+        return fail(c, LDA_ERR_STATE, "lda_sweep_pass_ms: no timed two-pass sweep has run");
+    LDA_HIP(c, hipEventSynchronize(c->pass_ev[2]));
+    LDA_HIP(c, hipEventElapsedTime(word_pass_ms, c->pass_ev[0], c->pass_ev[1]));
+    LDA_HIP(c, hipEventElapsedTime(doc_pass_ms, c->pass_ev[1], c->pass_ev[2]));
     return LDA_OK;
 }
 

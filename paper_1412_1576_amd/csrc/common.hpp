@@ -67,6 +67,10 @@ struct lda_ctx {
     int4* d_mix_items = nullptr;  // items (w, p0, n, 0) of mixture words whose row is rebuilt in LDS
     int4* d_gather_pieces = nullptr;
     int32_t n_row_items = 0, n_mix_items = 0, n_gather_pieces = 0;
+    // option time_sweep_passes: events before the word pass, between the passes and after
+    // the doc pass's tile kernel
+    hipEvent_t pass_ev[3] = {nullptr, nullptr, nullptr};
+    bool pass_ev_recorded = false;
     int32_t* d_woff = nullptr;  // [V+1] segment offsets
     // model
     int32_t* d_nkw = nullptr;   // [V*K] word-topic counts (dense rows)

@@ -653,6 +653,12 @@ template <int NW, int ND>
 int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
 {
     int rc;
+    const bool timed = c->opt.time_sweep_passes != 0;
+    if (timed) {
+        for (hipEvent_t& e : c->pass_ev)
+            if (!e) LDA_HIP(c, hipEventCreate(&e));
+        LDA_HIP(c, hipEventRecord(c->pass_ev[0], c->stream));
+    }
     if (need_proposals) {
         hipLaunchKernelGGL((doc_proposals_kernel<NW, ND>), dim3(xcd_grid(c->n_chunks)), dim3(256), 0,
                            c->stream, A);
@@ -682,6 +688,7 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
             hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND, 2>), grid, dim3(256), 0, c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
+    if (timed) LDA_HIP(c, hipEventRecord(c->pass_ev[1], c->stream));
     if (c->n_chunks > 0) {
         const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
         const int tpt = tokens_per_thread(c);
@@ -689,6 +696,10 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
            : tpt <= 2 ? launch_doc_tiles<NW, ND, 2>(c, A, lds)
                       : launch_doc_tiles<NW, ND, 4>(c, A, lds);
         if (rc != LDA_OK) return rc;
+    }
+    if (timed) {
+        LDA_HIP(c, hipEventRecord(c->pass_ev[2], c->stream));
+        c->pass_ev_recorded = true;
     }
     if (c->n_long > 0) {
         hipLaunchKernelGGL((doc_pass_long_kernel<NW, ND>), dim3(c->n_long), dim3(1024), 0, c->stream,

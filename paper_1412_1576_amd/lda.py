@@ -22,7 +22,8 @@ LDA_ERR_HIP = -4
 LDA_ERR_UNSUPPORTED = -5
 
 EXPORTS = [
-    "lda_init", "lda_build_alias", "lda_sweep", "lda_rebuild_counts", "lda_loglik",
+    "lda_init", "lda_build_alias", "lda_sweep", "lda_sweep_pass_ms", "lda_rebuild_counts",
+    "lda_loglik",
     "lda_num_tokens", "lda_sweep_index", "lda_get_z", "lda_set_z", "lda_get_nk",
     "lda_get_nkw_row", "lda_get_ndk_row", "lda_get_alias_row", "lda_get_sparse_table",
     "lda_get_beta_table", "lda_sync", "lda_last_error", "lda_destroy",
@@ -38,7 +39,8 @@ class lda_options(C.Structure):
         ("sweep_chunk_tokens", C.c_int32),
         ("sweep_block_threads", C.c_int32),
         ("rebuild_tile_tokens", C.c_int32),
-        ("reserved", C.c_int32 * 9),
+        ("time_sweep_passes", C.c_int32),
+        ("reserved", C.c_int32 * 8),
     ]
 
 
@@ -75,6 +77,7 @@ def load_library():
                                C.c_double, C.c_double, C.c_uint64, C.POINTER(lda_options)]),
         "lda_build_alias": (C.c_int, [vp]),
         "lda_sweep": (C.c_int, [vp, C.c_int32]),
+        "lda_sweep_pass_ms": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
         "lda_rebuild_counts": (C.c_int, [vp]),
         "lda_loglik": (C.c_int, [vp, dp, dp, dp]),
         "lda_num_tokens": (C.c_int64, [vp]),
@@ -107,7 +110,7 @@ class Lda:
 
     def __init__(self, doc_offsets, word_ids, V, K, alpha, beta, seed=0, stream=None,
                  dense_rows=0, dense_alias_min_count=0, proposal_mode=0, sweep_chunk_tokens=0,
-                 sweep_block_threads=0, rebuild_tile_tokens=0):
+                 sweep_block_threads=0, rebuild_tile_tokens=0, time_sweep_passes=0):
         L = load_library()
         self._h = C.c_void_p()
         doc_offsets = np.ascontiguousarray(doc_offsets, np.int64)
@@ -120,6 +123,7 @@ class Lda:
         opt.sweep_chunk_tokens = sweep_chunk_tokens
         opt.sweep_block_threads = sweep_block_threads
         opt.rebuild_tile_tokens = rebuild_tile_tokens
+        opt.time_sweep_passes = time_sweep_passes
         self.D = len(doc_offsets) - 1
         self.V, self.K = int(V), int(K)
         rc = L.lda_init(C.byref(self._h), self.D, self.V, self.K, doc_offsets, word_ids,
@@ -148,6 +152,11 @@ class Lda:
 
     def sweep(self, mh_steps):
         self._ck(_lib.lda_sweep(self._h, int(mh_steps)))
+
+    def sweep_pass_ms(self):
+        w, d = C.c_float(), C.c_float()
+        self._ck(_lib.lda_sweep_pass_ms(self._h, C.byref(w), C.byref(d)))
+        return w.value, d.value
 
     def rebuild_counts(self):
         self._ck(_lib.lda_rebuild_counts(self._h))
