@@ -488,11 +488,11 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
 // word-major records, which the tokens of a frequent word read (8 records a line) and
 // write (16 a line) one after the other -- every record line evicted before it is complete
 // costs a partial write to memory.
-// Up to two tokens per thread in 256-thread blocks (the default tiling) are compiled for
-// 7 waves per SIMD: one more resident workgroup per CU hides more of the gather latency
+// Chains of up to two steps with up to two tokens per thread in 256-thread blocks (the
+// default tiling) are compiled for 7 waves per SIMD: one more resident workgroup per CU hides more of the gather latency
 // than the few registers it costs.
 template <int NW, int ND, int T, int MAXB>
-__global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256) ? 7 : 1) void doc_pass_tiles_kernel(SplitArgs A)
+__global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256 && NW + ND <= 2) ? 7 : 1) void doc_pass_tiles_kernel(SplitArgs A)
 {
     using C = Chain<NW, ND>;
     extern __shared__ int32_t smem[];
