@@ -24,13 +24,16 @@ def lda_mod():
     return lda
 
 
-def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12, seed=123):
+def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12, seed=123,
+                  min_count=0):
+    """min_count > 0: words with fewer tokens draw from the mixture (bench.py's default form)."""
     rng = np.random.default_rng(seed)
     doff, words = corpus.make_corpus(cfg)
     N = int(doff[-1])
-    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed)
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                    dense_alias_min_count=min_count)
     o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                          lazy_alias=True)
+                          dense_alias_min_count=min_count, lazy_alias=True)
     # initial state: exhaustive
     z_init = g.get_z()
     assert np.array_equal(z_init, o.get_z())
@@ -47,7 +50,16 @@ def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12,
     # alias tables of the sampled words
     g.build_alias()
     o.build_alias()
+    if min_count:
+        assert g.get_beta_table()[2:] == o.get_beta_table()[2:]
     for w in sample_words:
+        if min_count and freq[w] < min_count:   # mixture word: its own table over its non-zeros
+            t, sp, at, c, qs = g.get_sparse_table(w)
+            ot, osp, oal, oc, oqs = o.get_sparse_table(w)
+            assert np.array_equal(t, ot) and np.array_equal(sp, osp), "mixture table %d" % w
+            assert len(t) == 0 or ((c, qs) == (oc, oqs) and
+                                   np.array_equal(at, ot[oal.astype(np.int64)])), "mixture table %d" % w
+            continue
         sg, ag, cg = g.get_alias_row(w)
         so, ao, co = o.get_alias_row(w)
         assert cg == co and np.array_equal(sg, so) and np.array_equal(ag, ao), "alias row %d" % w
@@ -91,6 +103,14 @@ def test_c3_full_size_sampled(lda_mod, oracle_mod):
     """The benchmark's workload (K = 10,000), with the config's own 4 MH steps."""
     cfg = corpus.CONFIGS["c3"]
     sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10)
+
+
+@pytest.mark.timeout(900)
+def test_c3_full_size_bench_configuration(lda_mod, oracle_mod):
+    """The workload exactly as bench.py times it: 2 steps, dense tables for words with at
+    least K tokens, the mixture for the others."""
+    cfg = corpus.CONFIGS["c3"]
+    sampled_check(lda_mod, oracle_mod, cfg, 2, n_tokens=1500, n_words=10, min_count=cfg.K)
 
 
 def property_check(lda_mod, cfg, dense_rows, mh_steps, seed=5):

@@ -233,6 +233,28 @@ def test_chain_shape_changes_between_sweeps(lda_mod, oracle_mod):
         g.close(); o.close()
 
 
+def test_sweep_pass_times(lda_mod):
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=200)
+    doff, words = corpus.make_corpus(cfg)
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, time_sweep_passes=1)
+    with pytest.raises(lda_mod.LdaError) as e:
+        g.sweep_pass_ms()                      # no sweep yet
+    assert e.value.code == lda_mod.LDA_ERR_STATE
+    g.build_alias(); g.sweep(2)
+    word_ms, doc_ms = g.sweep_pass_ms()
+    assert 0.0 < word_ms < 1e3 and 0.0 < doc_ms < 1e3
+    g.rebuild_counts(); g.build_alias(); g.sweep(5)   # five steps run as one fused kernel
+    with pytest.raises(lda_mod.LdaError) as e:
+        g.sweep_pass_ms()
+    assert e.value.code == lda_mod.LDA_ERR_STATE
+    g.close()
+    h = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta)
+    h.build_alias(); h.sweep(2)
+    with pytest.raises(lda_mod.LdaError):
+        h.sweep_pass_ms()                      # option off
+    h.close()
+
+
 def test_proposal_ablation_qualitative(lda_mod):
     """The paper's ablation (Sec. 7, cycle vs doc-only vs word-only proposals): with few MH
     steps the word-proposal alone sparsifies the word-topic table (best word-likelihood, worst
