@@ -153,6 +153,24 @@ __device__ __forceinline__ int32_t xcd_contiguous(int32_t n_items)
 
 unsigned xcd_grid(int32_t n_items) { return (unsigned)((n_items + kXcds - 1) / kXcds * kXcds); }
 
+// The word pass's work lists are in word order, and the cost of an item depends on its
+// word's class (frequent words are served from LDS or L2, rare ones miss), so contiguous
+// eighths would leave the XCDs unevenly loaded.  Runs of `run` consecutive items are dealt
+// to the XCDs in turn instead: neighbours still share an L2, every XCD sees every class.
+__device__ __forceinline__ int32_t xcd_runs(int32_t run)
+{
+    const int32_t xcd = (int32_t)(blockIdx.x % kXcds), seq = (int32_t)(blockIdx.x / kXcds);
+    return ((seq / run) * kXcds + xcd) * run + seq % run;
+}
+
+unsigned xcd_runs_grid(int32_t n_items, int32_t run)
+{
+    const int32_t runs = (n_items + run - 1) / run;
+    return (unsigned)((runs + kXcds - 1) / kXcds * kXcds * run);
+}
+
+constexpr int32_t kRowItemRun = 8, kMixItemRun = 16, kPieceRun = 64;
+
 // Eq. (9), (12): the topic of a random token of the document, or a uniform topic.
 // zat(j) is the snapshot topic of the document's j-th token.
 template <class ZAt>
@@ -208,7 +226,7 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     extern __shared__ int32_t smem[];
     uint2* __restrict__ tab = reinterpret_cast<uint2*>(smem);  // [K] (split, alias)
     int32_t* __restrict__ row = smem + 2 * (size_t)A.K;        // [K] n_kw
-    const int32_t it_i = xcd_contiguous(A.n_row_items);
+    const int32_t it_i = xcd_runs(kRowItemRun);
     if (it_i >= A.n_row_items) return;
     const int4 it = A.row_items[it_i];  // (w, p0, n, 0)
     const int32_t K = A.K;
@@ -251,14 +269,28 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     }
 }
 
+// The word of word-major position p inside a piece: the last w with off[w] <= p, where
+// off[0..nwords] are the piece's word offsets (off[0] <= p < off[nwords]).
+__device__ __forceinline__ int32_t piece_word(const int32_t* off, int32_t nwords, int32_t p)
+{
+    int32_t lo = 0, hi = nwords;
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (off[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // One piece = tokens [p0, p0 + n) that belong to words [w0, w1).  STORE 0: every word
-// has a dense row and a dense table; 1, 2: hybrid store (word_side.hpp).
+// has a dense row and a dense table; 1, 2: hybrid store (word_side.hpp).  The hybrid
+// form advances U tokens per thread together, stage by stage, so that their gathers
+// (word record, first probe of every n_kw lookup, table bin) are in flight at once.
 template <int NW, int ND, int STORE>
 __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
 {
     using C = Chain<NW, ND>;
     __shared__ int32_t soff[kPieceWords + 1];
-    const int32_t pc_i = xcd_contiguous(A.n_pieces);
+    const int32_t pc_i = xcd_runs(kPieceRun);
     if (pc_i >= A.n_pieces) return;
     const int4 pc = A.pieces[pc_i];  // (w0, w1, p0, n)
     const int32_t nwords = pc.y - pc.x;
@@ -266,21 +298,14 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int32_t i = tid; i <= nwords; i += nt) soff[i] = A.woff[pc.x + i];
     __syncthreads();
-    BetaTable bt{};
-    if constexpr (STORE != 0 && NW > 0) bt = load_beta_table(A);
-    for (int32_t i = tid; i < pc.w; i += nt) {
-        const int32_t p = pc.z + i;
-        int32_t lo = 0, hi = nwords;  // soff[lo] <= p < soff[hi]
-        while (hi - lo > 1) {
-            const int32_t mid = (lo + hi) >> 1;
-            if (soff[mid] <= p) lo = mid; else hi = mid;
-        }
-        const int32_t w = pc.x + lo;
-        int32_t zt[C::S], out[C::R];
-        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+    if constexpr (STORE == 0) {
+        for (int32_t i = tid; i < pc.w; i += nt) {
+            const int32_t p = pc.z + i;
+            const int32_t w = pc.x + piece_word(soff, nwords, p);
+            int32_t zt[C::S], out[C::R];
+            load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
 #pragma unroll
-        for (int k = 0; k < C::R; ++k) out[k] = 0;
-        if constexpr (STORE == 0) {
+            for (int k = 0; k < C::R; ++k) out[k] = 0;
             const size_t wk = (size_t)w * (size_t)K;
             out[0] = A.nkw[wk + (size_t)zt[0]];
             if constexpr (NW > 0) {
@@ -300,27 +325,69 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
             }
 #pragma unroll
             for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
-        } else {
-            const WordSide wv = load_word<STORE>(A, w);
-            out[0] = nkw_lookup<STORE>(wv, zt[0]);
-            if constexpr (NW > 0) {
-                const uint32_t g = (uint32_t)A.gid[p];
+            store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+        }
+    } else {
+        constexpr int U = 2;
+        BetaTable bt{};
+        if constexpr (NW > 0) bt = load_beta_table(A);
+        for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
+            int32_t p[U], zt[U][C::S], out[U][C::R];
+            bool live[U];
+            WordSide wv[U];
+            uint32_t g[U];
 #pragma unroll
-                for (int k = 0; k < NW; ++k) {
+            for (int u = 0; u < U; ++u) {
+                // lanes past the end of the piece redo its last token and drop the result
+                int32_t i = i0 + u * nt + tid;
+                live[u] = i < pc.w;
+                if (!live[u]) i = pc.w - 1;
+                p[u] = pc.z + i;
+                load_ints<C::S>(A.zt + ((size_t)p[u] << C::zt_shift), zt[u]);
+                g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
+                wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
+#pragma unroll
+                for (int k = 0; k < C::R; ++k) out[u][k] = 0;
+            }
+            NkwProbe pr[U][1 + ND];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k <= ND; ++k) pr[u][k] = nkw_probe_begin<STORE>(wv[u], zt[u][k]);
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                WordDraw d[U];
+                uint4 e[U];
+                int32_t t[U], nwt[U];
+                bool known[U];
+                NkwProbe pb[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
                     uint32_t x[4];
-                    philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                    WordDraw d;
-                    const uint4 e = *word_draw_address(wv, bt, (uint32_t)K, x[0], x[1], x[3], d);
-                    int32_t t, nwt;
-                    if (!word_draw_decode(d, e, t, nwt)) nwt = nkw_lookup<STORE>(wv, t);
-                    out[C::rec_topic(k)] = t;
-                    out[C::rec_topic(k) + 1] = nwt;
+                    philox4x32_10(g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                    e[u] = *word_draw_address(wv[u], bt, (uint32_t)K, x[0], x[1], x[3], d[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    known[u] = word_draw_decode(d[u], e[u], t[u], nwt[u]);
+                    if (!known[u]) pb[u] = nkw_probe_begin<STORE>(wv[u], t[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (!known[u]) nwt[u] = nkw_probe_finish<STORE>(wv[u], t[u], pb[u]);
+                    out[u][C::rec_topic(k)] = t[u];
+                    out[u][C::rec_topic(k) + 1] = nwt[u];
                 }
             }
 #pragma unroll
-            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = nkw_lookup<STORE>(wv, zt[1 + k]);
+            for (int u = 0; u < U; ++u) {
+                out[u][0] = nkw_probe_finish<STORE>(wv[u], zt[u][0], pr[u][0]);
+#pragma unroll
+                for (int k = 0; k < ND; ++k)
+                    out[u][C::rec_doc(k)] = nkw_probe_finish<STORE>(wv[u], zt[u][1 + k], pr[u][1 + k]);
+                if (live[u]) store_ints<C::R>(A.rec + ((size_t)p[u] << C::rec_shift), out[u]);
+            }
         }
-        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
     }
 }
 
@@ -334,7 +401,7 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
     using C = Chain<NW, ND>;
     extern __shared__ int32_t smem[];
     int32_t* __restrict__ row = smem;  // [K] n_kw
-    const int32_t it_i = xcd_contiguous(A.n_mix_items);
+    const int32_t it_i = xcd_runs(kMixItemRun);
     if (it_i >= A.n_mix_items) return;
     const int4 it = A.mix_items[it_i];  // (w, p0, n, 0)
     const int32_t K = A.K, w = it.x;
@@ -668,18 +735,18 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
         auto kern = word_pass_rows_kernel<NW, ND>;
         const size_t lds = sizeof(int32_t) * 3 * (size_t)c->K;
         if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
-        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_row_items)), dim3(1024), lds, c->stream, A);
+        hipLaunchKernelGGL(kern, dim3(xcd_runs_grid(c->n_row_items, kRowItemRun)), dim3(1024), lds, c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
     if (c->n_mix_items > 0) {
         auto kern = word_pass_mix_rows_kernel<NW, ND>;
         const size_t lds = sizeof(int32_t) * (size_t)c->K;
         if ((rc = raise_lds_limit(c, kern, lds)) != LDA_OK) return rc;
-        hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_mix_items)), dim3(512), lds, c->stream, A);
+        hipLaunchKernelGGL(kern, dim3(xcd_runs_grid(c->n_mix_items, kMixItemRun)), dim3(512), lds, c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
     if (c->n_gather_pieces > 0) {
-        const dim3 grid(xcd_grid(c->n_gather_pieces));
+        const dim3 grid(xcd_runs_grid(c->n_gather_pieces, kPieceRun));
         if (!c->hybrid)
             hipLaunchKernelGGL((word_pass_gather_kernel<NW, ND, 0>), grid, dim3(256), 0, c->stream, A);
         else if (c->H == c->V)

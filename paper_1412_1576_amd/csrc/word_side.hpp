@@ -58,6 +58,46 @@ __device__ __forceinline__ int32_t nkw_lookup(const WordSide& v, int32_t t)
     return 0;
 }
 
+// The same lookup in two halves, so that a caller can keep several in flight: the first
+// half issues the load of the dense entry or of the first hash slot, the second half
+// resolves it (and probes on in the rare case the first slot holds another topic).
+struct NkwProbe {
+    uint2 e;
+    uint32_t slot;
+};
+
+template <int STORE>
+__device__ __forceinline__ NkwProbe nkw_probe_begin(const WordSide& v, int32_t t)
+{
+    NkwProbe p;
+    if (STORE != 2 || (v.kind & 1u)) {
+        p.slot = 0;
+        p.e = make_uint2((uint32_t) static_cast<const int32_t*>(v.row)[t], 0u);
+    } else {
+        p.slot = row_hash_slot(t, v.lg);
+        p.e = static_cast<const uint2*>(v.row)[p.slot];
+    }
+    return p;
+}
+
+template <int STORE>
+__device__ __forceinline__ int32_t nkw_probe_finish(const WordSide& v, int32_t t, const NkwProbe& p)
+{
+    if (STORE != 2 || (v.kind & 1u)) return (int32_t)p.e.x;
+    if (p.e.x == (uint32_t)t) return (int32_t)p.e.y;
+    if (p.e.x == 0xFFFFFFFFu) return 0;
+    const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
+    const uint32_t mask = (1u << v.lg) - 1u;
+    uint32_t s = (p.slot + 1) & mask;
+    for (uint32_t i = 1; i <= mask; ++i) {
+        const uint2 e = row[s];
+        if (e.x == (uint32_t)t) return (int32_t)e.y;
+        if (e.x == 0xFFFFFFFFu) return 0;
+        s = (s + 1) & mask;
+    }
+    return 0;
+}
+
 // The shared table of the mixture's beta term: (split, alias) bins read as aligned pairs.
 struct BetaTable {
     const uint4* pairs;
