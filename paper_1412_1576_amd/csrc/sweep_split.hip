@@ -472,89 +472,90 @@ struct LongDoc {  // document hashed in the global workspace
 };
 
 // The chains of T tokens of one thread, advanced together stage by stage.  doc[u] is
-// token u's document, own[u] its position in it, g[u] its CSR position (the Philox
-// counter), r[u] its word-pass record.
+// token u's document, g[u] its CSR position (the Philox counter), r[u] its word-pass record, z0[u] its snapshot topic and nd0[u] = n_kd of it.
 template <int NW, int ND, int T, class DocView>
 __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocView (&doc)[T],
-                                                const uint32_t (&own)[T], const uint32_t (&g)[T],
+                                                const uint32_t (&g)[T],
                                                 const int32_t (&r)[T][Chain<NW, ND>::R],
+                                                const int32_t (&z0)[T], const int32_t (&nd0)[T],
                                                 int32_t (&s)[T])
 {
 #pragma clang fp contract(off)
     using C = Chain<NW, ND>;
-    int32_t z0[T], nds[T], nws[T], nks[T];
+    int32_t nds[T], nws[T], nks[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
-        doc[u].token(own[u], z0[u], nds[u]);
+        nds[u] = nd0[u];
         s[u] = z0[u];
         nks[u] = A.nk[z0[u]];
         nws[u] = r[u][0];
     }
+    // Proposals do not depend on the chain's state, so every step's proposal, its n_kd probe
+    // and its n_k gather are issued before the first accept test: one round trip to L2
+    // for all of them instead of one per step.
+    uint32_t x2[C::M][T];
+    int32_t t[C::M][T], ndt[C::M][T], nwt[C::M][T], nkt[C::M][T];
 #pragma unroll
     for (int j = 0; j < C::M; ++j) {
         const bool word_step = C::is_word(j);
         const int i = C::index(j);
-        uint32_t x2[T];
-        int32_t t[T], ndt[T], nwt[T], nkt[T];
 #pragma unroll
         for (int u = 0; u < T; ++u) {
             uint32_t x[4];
             philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
-            x2[u] = x[2];
+            x2[j][u] = x[2];
             if (word_step) {
-                t[u] = r[u][C::rec_topic(i)];
-                nwt[u] = r[u][C::rec_topic(i) + 1];
-                ndt[u] = doc[u].count(t[u]);
+                t[j][u] = r[u][C::rec_topic(i)];
+                nwt[j][u] = r[u][C::rec_topic(i) + 1];
+                ndt[j][u] = doc[u].count(t[j][u]);
             } else {
                 const double u0 = unit_open(x[0]);
                 const double Ld = (double)doc[u].L;
                 if (u0 * (Ld + A.alphabar) < Ld) {
-                    doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[u], ndt[u]);
+                    doc[u].token(mulhi32(x[1], (uint32_t)doc[u].L), t[j][u], ndt[j][u]);
                 } else {
-                    t[u] = (int32_t)mulhi32(x[1], (uint32_t)A.K);
-                    ndt[u] = doc[u].count(t[u]);
+                    t[j][u] = (int32_t)mulhi32(x[1], (uint32_t)A.K);
+                    ndt[j][u] = doc[u].count(t[j][u]);
                 }
-                nwt[u] = r[u][C::rec_doc(i)];
+                nwt[j][u] = r[u][C::rec_doc(i)];
             }
-            nkt[u] = A.nk[t[u]];
+            nkt[j][u] = A.nk[t[j][u]];
         }
+    }
+#pragma unroll
+    for (int j = 0; j < C::M; ++j) {
+        const bool word_step = C::is_word(j);
 #pragma unroll
         for (int u = 0; u < T; ++u) {
+            const int32_t tt = t[j][u], nd_t = ndt[j][u], nw_t = nwt[j][u], nk_t = nkt[j][u];
             const int32_t ms = (s[u] == z0[u]) ? 1 : 0;
-            const int32_t mt = (t[u] == z0[u]) ? 1 : 0;
+            const int32_t mt = (tt == z0[u]) ? 1 : 0;
             // Eq. (4) ratio p(t)/p(s), the token removed at its snapshot topic
-            double num = (double)(ndt[u] - mt) + A.alpha;
-            num = num * ((double)(nwt[u] - mt) + A.beta);
+            double num = (double)(nd_t - mt) + A.alpha;
+            num = num * ((double)(nw_t - mt) + A.beta);
             num = num * ((double)(nks[u] - ms) + A.betabar);
             double den = (double)(nds[u] - ms) + A.alpha;
             den = den * ((double)(nws[u] - ms) + A.beta);
-            den = den * ((double)(nkt[u] - mt) + A.betabar);
+            den = den * ((double)(nk_t - mt) + A.betabar);
             if (word_step) {  // Eq. (8): times p_w(s)/p_w(t)
                 num = num * ((double)nws[u] + A.beta);
-                num = num * ((double)nkt[u] + A.betabar);
-                den = den * ((double)nwt[u] + A.beta);
+                num = num * ((double)nk_t + A.betabar);
+                den = den * ((double)nw_t + A.beta);
                 den = den * ((double)nks[u] + A.betabar);
             } else {          // Eq. (11): times p_d(s)/p_d(t)
                 num = num * ((double)nds[u] + A.alpha);
-                den = den * ((double)ndt[u] + A.alpha);
+                den = den * ((double)nd_t + A.alpha);
             }
-            const double uu = unit_open(x2[u]);
-            const bool accept = (t[u] != s[u]) && (uu * den < num);
-            s[u] = accept ? t[u] : s[u];
-            nds[u] = accept ? ndt[u] : nds[u];
-            nws[u] = accept ? nwt[u] : nws[u];
-            nks[u] = accept ? nkt[u] : nks[u];
+            const double uu = unit_open(x2[j][u]);
+            const bool accept = (tt != s[u]) && (uu * den < num);
+            s[u] = accept ? tt : s[u];
+            nds[u] = accept ? nd_t : nds[u];
+            nws[u] = accept ? nw_t : nws[u];
+            nks[u] = accept ? nk_t : nks[u];
         }
     }
 }
 
-// T = tokens per thread; a tile has at most T * blockDim.x tokens.
-//
-// The token streams (z, document indices, word-major positions, the new z) are read and
-// written once, with the streaming hint: what should stay in L2 are the lines of
-// word-major records, which the tokens of a frequent word read (8 records a line) and
-// write (16 a line) one after the other -- every record line evicted before it is complete
-// costs a partial write to memory.
 // Chains of up to two steps with up to two tokens per thread in 256-thread blocks (the
 // default tiling) are compiled for 7 waves per SIMD: one more resident workgroup per CU hides more of the gather latency
 // than the few registers it costs.
@@ -571,7 +572,7 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256 && NW + ND <= 2) ? 7 :
     // the word-pass records do not depend on the tile: their gather (one random line per
     // token) is issued first and overlaps the staging of the documents
     const int32_t tok0 = A.doff[d0];
-    uint32_t own[T], g[T];
+    uint32_t g[T];
     int32_t wp[T], s[T], idx[T], r[T][C::R];
     bool live[T];
 #pragma unroll
@@ -586,18 +587,48 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256 && NW + ND <= 2) ? 7 :
     }
 #pragma unroll
     for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
-    const DocTile tile = load_doc_tile<true>(smem, A.cap_tokens, A.z, A.doff, A.tokdoc, d0, d1);
+    // Stage the documents as load_doc_tile does (doc_tile.hpp: same LDS layout, same tables),
+    // but keep what each thread learns about its own tokens in registers: the thread that
+    // inserts a token into its document's table is the one that runs its chain.
+    DocTile tile;
+    tile.zs = reinterpret_cast<uint32_t*>(smem);
+    tile.tab = reinterpret_cast<uint32_t*>(smem + A.cap_tokens);
+    tile.sdoff = smem + 3 * (size_t)A.cap_tokens;
+    tile.nd = d1 - d0;
+    tile.tok0 = tok0;
+    tile.ntok = ntok;
+    int32_t z0[T], dl[T], nd0[T];
+    uint32_t slot[T];
+    for (int32_t i = threadIdx.x; i <= tile.nd; i += blockDim.x) tile.sdoff[i] = A.doff[d0 + i] - tok0;
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        z0[u] = __builtin_nontemporal_load(&A.z[g[u]]);
+        dl[u] = (int32_t)__builtin_nontemporal_load(&A.tokdoc[g[u]]);
+        if (live[u]) {
+            tile.zs[idx[u]] = (uint32_t)z0[u];
+            reinterpret_cast<uint2*>(tile.tab)[idx[u]] = make_uint2(kEmptySlot, kEmptySlot);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (live[u]) {
+            slot[u] = tile.table(dl[u]).insert(z0[u]);
+            tile.zs[idx[u]] = (uint32_t)z0[u] | (slot[u] << kTopicBits);  // own element only
+        }
+    }
+    __syncthreads();
     TileDoc doc[T];
 #pragma unroll
     for (int u = 0; u < T; ++u) {
-        const int32_t dl = (int32_t)__builtin_nontemporal_load(&A.tokdoc[g[u]]);
-        const int32_t b = tile.sdoff[dl];
-        doc[u].L = tile.sdoff[dl + 1] - b;
-        doc[u].tab = tile.table(dl);
+        const int32_t b = tile.sdoff[dl[u]];
+        doc[u].L = tile.sdoff[dl[u] + 1] - b;
+        doc[u].tab = tile.table(dl[u]);
         doc[u].zs = tile.zs + b;
-        own[u] = (uint32_t)(idx[u] - b);
+        if (!live[u]) slot[u] = tile.zs[idx[u]] >> kTopicBits;  // a clone of the last token
+        nd0[u] = doc[u].tab.count_at(slot[u]);
     }
-    doc_pass_chains<NW, ND, T>(A, doc, own, g, r, s);
+    doc_pass_chains<NW, ND, T>(A, doc, g, r, z0, nd0, s);
 #pragma unroll
     for (int u = 0; u < T; ++u)
         if (live[u]) __builtin_nontemporal_store(s[u], &A.znew[g[u]]);
@@ -657,7 +688,10 @@ __global__ __launch_bounds__(1024) void doc_pass_long_kernel(SplitArgs A)
         int32_t r[T][C::R];
 #pragma unroll
         for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
-        doc_pass_chains<NW, ND, T>(A, doc, own, g, r, s);
+        int32_t z0[T], nd0[T];
+#pragma unroll
+        for (int u = 0; u < T; ++u) doc[u].token(own[u], z0[u], nd0[u]);
+        doc_pass_chains<NW, ND, T>(A, doc, g, r, z0, nd0, s);
 #pragma unroll
         for (int u = 0; u < T; ++u)
             if (live[u])
