@@ -182,7 +182,7 @@ int launch_dense_rows(lda_ctx* c)
         LDA_HIP(c, hipGetLastError());
     }
     hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
-                       dim3(span <= 512 ? 256 : 512), lds, c->stream, c->d_tiles, c->d_zt,
+                       dim3(span <= 512 ? 256 : (span <= 16384 ? 512 : 1024)), lds, c->stream, c->d_tiles, c->d_zt,
                        c->zt_shift, K, span,
                        c->d_nkw, c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz);
     LDA_HIP(c, hipGetLastError());
