@@ -373,6 +373,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_wpos, (size_t)N, "word-major positions"));
     TRY(dev_alloc(c, &c->d_zt, (size_t)N, "word-major z"));
     c->zt_ints = (size_t)N;
+    c->zt_pack16 = K <= 65536;
+    c->zt_mask = c->zt_pack16 ? 0xFFFFu : 0xFFFFFFFFu;
     TRY(dev_alloc(c, &c->d_woff, (size_t)V + 1, "word offsets"));
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
     TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));

@@ -49,11 +49,15 @@ struct lda_ctx {
     // word-major view
     int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order
     int32_t* d_wpos = nullptr;  // [N] word-major position of token g (inverse of gid)
-    // Word-major token records of 2^zt_shift ints: [0] the token's z, [1 + i] the topic that
-    // doc step i of the coming sweep proposes for it (when td_valid).
+    // Word-major token records of 2^zt_shift ints.  Fields: the token's z, then the topic that
+    // doc step i of the coming sweep proposes for it (when td_valid); one int per field, or,
+    // with zt_pack16 (K <= 65536), two 16-bit fields per int.  The z field is the low
+    // zt_mask bits of the record's first int.
     int32_t* d_zt = nullptr;
     size_t zt_ints = 0;         // allocated ints
     int32_t zt_shift = 0;
+    bool zt_pack16 = false;
+    uint32_t zt_mask = 0xFFFFFFFFu;
     bool zt_current = false;    // record [0] equals d_z
     bool td_valid = false;      // the stored doc proposals are those of sweep td_sweep, drawn
     uint32_t td_sweep = 0;      //   from d_z, for a chain of td_nw word and td_nd doc steps

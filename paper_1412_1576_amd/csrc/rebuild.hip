@@ -48,7 +48,8 @@ __global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restr
 // blockIdx.x: tile; blockIdx.y: range of `span` topics (one range when the row fits LDS)
 __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __restrict__ tiles,
                                                          const int32_t* __restrict__ zw,
-                                                         int32_t sh, int32_t K, int32_t span,
+                                                         int32_t sh, uint32_t zmask, int32_t K,
+                                                         int32_t span,
                                                          int32_t* __restrict__ nkw,
                                                          const uint32_t* __restrict__ sp_off,
                                                          int32_t* __restrict__ sp_topic,
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
     for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
     __syncthreads();
     for (int32_t p = t.p0 + tid; p < t.p1; p += nt) {
-        const uint32_t r = (uint32_t)(zw[(size_t)p << sh] - k0);
+        const uint32_t r = ((uint32_t)zw[(size_t)p << sh] & zmask) - (uint32_t)k0;
         if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
     }
     __syncthreads();
@@ -183,7 +184,7 @@ int launch_dense_rows(lda_ctx* c)
     }
     hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
                        dim3(span <= 512 ? 256 : (span <= 16384 ? 512 : 1024)), lds, c->stream, c->d_tiles, c->d_zt,
-                       c->zt_shift, K, span,
+                       c->zt_shift, c->zt_mask, K, span,
                        c->d_nkw, c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
@@ -294,7 +295,7 @@ __device__ __forceinline__ uint32_t log2_pow2(uint32_t x) { return 31u - (uint32
 // fill the hash row.
 __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     const int32_t* __restrict__ words, int32_t P, const int32_t* __restrict__ woff,
-    const int32_t* __restrict__ zw, int32_t sh,
+    const int32_t* __restrict__ zw, int32_t sh, uint32_t zmask,
     const uint32_t* __restrict__ sp_off, int32_t* __restrict__ sp_topic,
     int32_t* __restrict__ sp_count, int32_t* __restrict__ sp_nnz,
     const uint32_t* __restrict__ hs_off, uint2* __restrict__ hs)
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
     }
     int32_t Q = 2;  // sort size: smallest power of two >= c
     while (Q < c) Q <<= 1;
-    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? zw[(size_t)(p0 + i) << sh] : kSortPad;
+    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? (int32_t)((uint32_t)zw[(size_t)(p0 + i) << sh] & zmask) : kSortPad;
     __syncthreads();
     for (int32_t k = 2; k <= Q; k <<= 1) {
         for (int32_t j = k >> 1; j > 0; j >>= 1) {
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __rest
                                                            int32_t n_words, int32_t tile,
                                                            const int32_t* __restrict__ woff,
                                                            const int32_t* __restrict__ zw,
-                                                           int32_t sh, int32_t K,
+                                                           int32_t sh, uint32_t zmask, int32_t K,
                                                            int32_t* __restrict__ scratch)
 {
     const int32_t wi = blockIdx.y;
@@ -382,7 +383,7 @@ __global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __rest
     for (int32_t b = p0 + (int32_t)blockIdx.x * tile; b < p1; b += (int32_t)gridDim.x * tile) {
         const int32_t e = (b + tile < p1) ? b + tile : p1;
         for (int32_t p = b + (int32_t)threadIdx.x; p < e; p += (int32_t)blockDim.x)
-            atomicAdd(&row[zw[(size_t)p << sh]], 1);
+            atomicAdd(&row[(uint32_t)zw[(size_t)p << sh] & zmask], 1);
     }
 }
 
@@ -453,6 +454,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
         const int threads = P <= 64 ? 64 : (P <= 512 ? 256 : 1024);
         hipLaunchKernelGGL(sparse_rows_sort_kernel, dim3(c->n_sortsp_class[cl]), dim3(threads), lds,
                            c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_zt, c->zt_shift,
+                           c->zt_mask,
                            c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz, c->d_hs_off,
                            c->d_hs);
         LDA_HIP(c, hipGetLastError());
@@ -461,7 +463,8 @@ int launch_rebuild_hybrid(lda_ctx* c)
     for (int32_t b0 = 0; b0 < c->n_bigsp; b0 += c->n_scratch_rows) {
         const int32_t nb = std::min(c->n_scratch_rows, c->n_bigsp - b0);
         hipLaunchKernelGGL(scratch_hist_kernel, dim3(64, nb), dim3(256), 0, c->stream,
-                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zt, c->zt_shift, K,
+                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zt, c->zt_shift, c->zt_mask,
+                           K,
                            c->d_scratch_rows);
         LDA_HIP(c, hipGetLastError());
         hipLaunchKernelGGL(scratch_compact_kernel, dim3(nb), dim3(1024), 0, c->stream,

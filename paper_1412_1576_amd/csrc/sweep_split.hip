@@ -54,9 +54,7 @@ template <int NW, int ND>
 struct Chain {
     static_assert(NW + ND >= 1 && (ND == 0 || NW == 0 || NW == ND || NW == ND + 1), "chain shape");
     static constexpr int M = NW + ND;
-    static constexpr int zt_shift = pow2_shift(1 + ND);
     static constexpr int rec_shift = pow2_shift(1 + 2 * NW + ND);
-    static constexpr int S = 1 << zt_shift;   // ints of a (z, doc proposals) record
     static constexpr int R = 1 << rec_shift;  // ints of a word-pass record
     __host__ __device__ static constexpr bool is_word(int j)
     {
@@ -116,6 +114,7 @@ struct SplitArgs {
     const uint4* alias;  // (split, alias, n_kw[bin], n_kw[alias]) per bin
     const uint32_t* cap;
     int32_t* zt;
+    int32_t zt_pack16;  // topics fit 16 bits: two fields of a (z, doc proposals) record per int
     int32_t* rec;
     const int4* row_items;
     const int4* pieces;
@@ -141,6 +140,51 @@ struct SplitArgs {
     int32_t* long_keys;
     int32_t* long_cnts;
 };
+
+// ints of a token's (z, doc proposals) record with nd doc proposals: one int per field, or,
+// when every topic fits 16 bits, two fields per int; rounded up to a power of two
+constexpr int zt_record_shift(int nd, bool pack16) { return pow2_shift(pack16 ? (2 + nd) / 2 : 1 + nd); }
+
+// v[0] = z, v[1 + i] = the topic doc step i proposes, of the token at word-major position p
+template <int ND>
+__device__ __forceinline__ void load_zt(const SplitArgs& A, size_t p, int32_t (&v)[1 + ND])
+{
+    if (A.zt_pack16) {
+        constexpr int W = 1 << zt_record_shift(ND, true);
+        int32_t w[W];
+        load_ints<W>(A.zt + p * W, w);
+#pragma unroll
+        for (int k = 0; k <= ND; ++k) v[k] = (int32_t)(((uint32_t)w[k >> 1] >> (16 * (k & 1))) & 0xFFFFu);
+    } else {
+        constexpr int W = 1 << zt_record_shift(ND, false);
+        int32_t w[W];
+        load_ints<W>(A.zt + p * W, w);
+#pragma unroll
+        for (int k = 0; k <= ND; ++k) v[k] = w[k];
+    }
+}
+
+template <int ND>
+__device__ __forceinline__ void store_zt(const SplitArgs& A, size_t p, const int32_t (&v)[1 + ND])
+{
+    if (A.zt_pack16) {
+        constexpr int W = 1 << zt_record_shift(ND, true);
+        int32_t w[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) w[k] = 0;
+#pragma unroll
+        for (int k = 0; k <= ND; ++k) w[k >> 1] |= (int32_t)((uint32_t)v[k] << (16 * (k & 1)));
+        store_ints<W>(A.zt + p * W, w);
+    } else {
+        constexpr int W = 1 << zt_record_shift(ND, false);
+        int32_t w[W];
+#pragma unroll
+        for (int k = 0; k < W; ++k) w[k] = 0;
+#pragma unroll
+        for (int k = 0; k <= ND; ++k) w[k] = v[k];
+        store_ints<W>(A.zt + p * W, w);
+    }
+}
 
 // Workgroups are dealt to the 8 XCDs round-robin.  Handing each XCD one contiguous run of
 // the items keeps neighbouring items -- which touch neighbouring word-major records -- in
@@ -197,9 +241,7 @@ __global__ __launch_bounds__(256) void doc_proposals_kernel(SplitArgs A)
     const int32_t tok0 = A.doff[d0], ntok = A.doff[d1] - tok0;
     for (int32_t i = threadIdx.x; i < ntok; i += blockDim.x) {
         const uint32_t g = (uint32_t)(tok0 + i);
-        int32_t row[C::S];
-#pragma unroll
-        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        int32_t row[1 + ND];
         row[0] = A.z[g];
         if constexpr (ND > 0) {
             const int32_t d = d0 + (int32_t)A.tokdoc[g];  // a long document is a tile of its own
@@ -212,7 +254,7 @@ __global__ __launch_bounds__(256) void doc_proposals_kernel(SplitArgs A)
                                           [&](uint32_t j) { return A.z[b + (int32_t)j]; });
             }
         }
-        store_ints<C::S>(A.zt + ((size_t)A.wpos[g] << C::zt_shift), row);
+        store_zt<ND>(A, (size_t)A.wpos[g], row);
     }
 }
 
@@ -241,20 +283,33 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     }
     __syncthreads();
     const uint32_t capw = A.cap[it.x];
-    for (int32_t i = tid; i < it.z; i += nt) {
-        const int32_t p = it.y + i;
-        int32_t zt[C::S], out[C::R];
-        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+    // U tokens per thread and round: their loads are issued together (the loop is bound by
+    // the latency of one load round trip per round at 4 waves per SIMD)
+    constexpr int U = 4;
+    for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
+        int32_t p[U], zt[U][1 + ND];
+        uint32_t g[U];
+        bool live[U];
 #pragma unroll
-        for (int k = 0; k < C::R; ++k) out[k] = 0;
-        out[0] = row[zt[0]];
-        if constexpr (NW > 0) {
-            const uint32_t g = (uint32_t)A.gid[p];
+        for (int u = 0; u < U; ++u) {
+            int32_t i = i0 + u * nt + tid;
+            live[u] = i < it.z;
+            if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
+            p[u] = it.y + i;
+            load_zt<ND>(A, (size_t)p[u], zt[u]);
+            g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int32_t out[C::R];
+#pragma unroll
+            for (int k = 0; k < C::R; ++k) out[k] = 0;
+            out[0] = row[zt[u][0]];
 #pragma unroll
             for (int k = 0; k < NW; ++k) {
                 // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
                 uint32_t x[4];
-                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
                 const uint32_t bin = mulhi32(x[0], (uint32_t)K);
                 const uint32_t rr = mulhi32(x[1], capw);
                 const uint2 e = tab[bin];
@@ -262,10 +317,10 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
                 out[C::rec_topic(k)] = t;
                 out[C::rec_topic(k) + 1] = row[t];
             }
-        }
 #pragma unroll
-        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
-        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[u][1 + k]];
+            if (live[u]) store_ints<C::R>(A.rec + ((size_t)p[u] << C::rec_shift), out);
+        }
     }
 }
 
@@ -302,8 +357,8 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
         for (int32_t i = tid; i < pc.w; i += nt) {
             const int32_t p = pc.z + i;
             const int32_t w = pc.x + piece_word(soff, nwords, p);
-            int32_t zt[C::S], out[C::R];
-            load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+            int32_t zt[1 + ND], out[C::R];
+            load_zt<ND>(A, (size_t)p, zt);
 #pragma unroll
             for (int k = 0; k < C::R; ++k) out[k] = 0;
             const size_t wk = (size_t)w * (size_t)K;
@@ -332,7 +387,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
         BetaTable bt{};
         if constexpr (NW > 0) bt = load_beta_table(A);
         for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
-            int32_t p[U], zt[U][C::S], out[U][C::R];
+            int32_t p[U], zt[U][1 + ND], out[U][C::R];
             bool live[U];
             WordSide wv[U];
             uint32_t g[U];
@@ -343,7 +398,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
                 live[u] = i < pc.w;
                 if (!live[u]) i = pc.w - 1;
                 p[u] = pc.z + i;
-                load_ints<C::S>(A.zt + ((size_t)p[u] << C::zt_shift), zt[u]);
+                load_zt<ND>(A, (size_t)p[u], zt[u]);
                 g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
                 wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
 #pragma unroll
@@ -419,8 +474,8 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
     if constexpr (NW > 0) bt = load_beta_table(A);
     for (int32_t i = tid; i < it.z; i += nt) {
         const int32_t p = it.y + i;
-        int32_t zt[C::S], out[C::R];
-        load_ints<C::S>(A.zt + ((size_t)p << C::zt_shift), zt);
+        int32_t zt[1 + ND], out[C::R];
+        load_zt<ND>(A, (size_t)p, zt);
 #pragma unroll
         for (int k = 0; k < C::R; ++k) out[k] = 0;
         out[0] = row[zt[0]];
@@ -642,9 +697,7 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256 && NW + ND <= 2) ? 7 :
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         if (!live[u]) continue;
-        int32_t row[C::S];
-#pragma unroll
-        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        int32_t row[1 + ND];
         row[0] = s[u];
 #pragma unroll
         for (int k = 0; k < ND; ++k) {
@@ -654,7 +707,7 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && MAXB <= 256 && NW + ND <= 2) ? 7 :
             row[1 + k] = doc_proposal(x[0], x[1], doc[u].L, A.K, A.alphabar,
                                       [&](uint32_t j) { return (int32_t)zs[j]; });
         }
-        store_ints<C::S>(A.zt + ((size_t)wp[u] << C::zt_shift), row);
+        store_zt<ND>(A, (size_t)wp[u], row);
     }
 }
 
@@ -700,9 +753,7 @@ __global__ __launch_bounds__(1024) void doc_pass_long_kernel(SplitArgs A)
     __syncthreads();  // the document's new assignment is complete
     for (int32_t i = threadIdx.x; i < Ld; i += blockDim.x) {
         const uint32_t g = (uint32_t)(tok0 + i);
-        int32_t row[C::S];
-#pragma unroll
-        for (int k = 0; k < C::S; ++k) row[k] = 0;
+        int32_t row[1 + ND];
         row[0] = __hip_atomic_load(&A.znew[g], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int k = 0; k < ND; ++k) {
@@ -713,7 +764,7 @@ __global__ __launch_bounds__(1024) void doc_pass_long_kernel(SplitArgs A)
                                          __HIP_MEMORY_SCOPE_AGENT);
             });
         }
-        store_ints<C::S>(A.zt + ((size_t)A.wpos[g] << C::zt_shift), row);
+        store_zt<ND>(A, (size_t)A.wpos[g], row);
     }
 }
 
@@ -915,12 +966,12 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
 {
     int32_t nw, nd;
     chain_shape(c->opt.proposal_mode, mh_steps, nw, nd);
-    const int zt_shift = pow2_shift(1 + nd), rec_shift = pow2_shift(1 + 2 * nw + nd);
+    const int zt_shift = zt_record_shift(nd, c->zt_pack16), rec_shift = pow2_shift(1 + 2 * nw + nd);
     int rc;
     if (c->zt_shift != zt_shift || c->zt_ints < ((size_t)c->N << zt_shift)) {
         c->zt_current = false;
         c->td_valid = false;
-        if ((rc = grow(c, &c->d_zt, &c->zt_ints, (size_t)c->N << zt_shift, "word-major records")) != LDA_OK)
+        if ((rc = grow(c, &c->d_zt, &c->zt_ints, ((size_t)c->N << zt_shift), "word-major records")) != LDA_OK)
             return rc;
         c->zt_shift = zt_shift;
     }
@@ -933,7 +984,7 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
     A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff; A.chunk_doc = c->d_chunk_doc;
     A.tokdoc = c->d_tokdoc; A.wpos = c->d_wpos; A.gid = c->d_gid; A.woff = c->d_woff;
     A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias; A.cap = c->d_cap;
-    A.zt = c->d_zt; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
+    A.zt = c->d_zt; A.zt_pack16 = c->zt_pack16 ? 1 : 0; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
     A.n_chunks = c->n_chunks; A.n_row_items = c->n_row_items; A.n_pieces = c->n_gather_pieces;
     A.K = c->K; A.cap_tokens = c->chunk_tokens;
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
