@@ -66,7 +66,7 @@ void free_all(lda_ctx* c)
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
     dev_free(c->d_flag);
     dev_free(c->d_dense_alias_words);
-    for (int i = 0; i < 5; ++i) dev_free(c->d_mix_class[i]);
+    for (int i = 0; i < kMixClasses; ++i) dev_free(c->d_mix_class[i]);
     for (int i = 0; i < 4; ++i) dev_free(c->d_sortsp_class[i]);
     dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
     dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
@@ -106,9 +106,8 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->h_wkind.resize(V);
     c->h_sp_off.assign((size_t)V + 1, 0);
     c->h_hs_off.assign((size_t)V + 1, 0);
-    std::vector<int32_t> dense_alias, mix, sparse, compact, bigsp, mixc[5], sortc[4];
+    std::vector<int32_t> dense_alias, mix, sparse, compact, bigsp, mixc[kMixClasses], sortc[4];
     std::vector<uint4> meta(2 * (size_t)V, make_uint4(0u, 0u, 0u, 0u));
-    static const int32_t mix_cap[4] = {64, 512, 4096, 0};
     static const int32_t sort_cap[4] = {64, 512, 4096, 16384};
     const int32_t lds_max = max_lds_table_entries();
     uint64_t list_total = 0, hash_total = 0;
@@ -136,11 +135,8 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
             const int32_t cap = std::min(cw, K);
             list_total += (uint64_t)cap;
             mix.push_back(w);
-            int cl = 4;
-            if (cap <= mix_cap[0]) cl = 0;
-            else if (cap <= mix_cap[1]) cl = 1;
-            else if (cap <= mix_cap[2]) cl = 2;
-            else if (cap <= lds_max) cl = 3;
+            int cl = 0;
+            while (kMixClassCap[cl] >= 0 && cap > (kMixClassCap[cl] ? kMixClassCap[cl] : lds_max)) ++cl;
             mixc[cl].push_back(w);
             if (dense_row) {
                 if (!list_from_rebuild(c, w)) compact.push_back(w);
@@ -181,7 +177,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     UP(d_sparse_words, sparse, "sparse-row words");
     UP(d_compact_words, compact, "compaction words");
     UP(d_bigsp_words, bigsp, "big sparse words");
-    for (int i = 0; i < 5; ++i) {
+    for (int i = 0; i < kMixClasses; ++i) {
         c->n_mix_class[i] = (int32_t)mixc[i].size();
         UP(d_mix_class[i], mixc[i], "mixture class");
     }
@@ -205,7 +201,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     LDA_HIP(c, hipMemsetAsync(c->d_sp_nnz, 0, sizeof(int32_t) * (size_t)V, c->stream));
     // global list memory for tables too large for LDS
     const bool need_big = (K > lds_max && (c->n_dense_alias > 0 || c->n_mix > 0)) ||
-                          c->n_mix_class[4] > 0;
+                          c->n_mix_class[kMixClasses - 1] > 0;
     if (need_big) {
         c->big_ws_stride = (alias_list_bytes_host((size_t)K) + 255) / 256 * 256;
         int64_t wg = (int64_t)(2.0e9 / (double)c->big_ws_stride);
@@ -460,11 +456,12 @@ int lda_build_alias(lda_ctx* c)
         return fail(c, LDA_ERR_STATE, "lda_build_alias: counts are stale (call lda_rebuild_counts)");
     int rc;
     if (c->hybrid) {
-        static const int32_t cap[5] = {64, 512, 4096, 0, 0};
         rc = launch_alias_build_hybrid(c);
-        for (int cl = 0; cl < 5 && rc == LDA_OK; ++cl)
+        for (int cl = 0; cl < kMixClasses && rc == LDA_OK; ++cl) {
+            const int32_t cap = kMixClassCap[cl];  // launch_alias_mix_class: 0 = global workspace
             rc = launch_alias_mix_class(c, c->d_mix_class[cl], c->n_mix_class[cl],
-                                        cl == 3 ? max_lds_table_entries() : cap[cl]);
+                                        cap < 0 ? 0 : (cap ? cap : max_lds_table_entries()));
+        }
     } else {
         rc = launch_alias_build(c);
     }

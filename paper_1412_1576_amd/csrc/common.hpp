@@ -19,6 +19,12 @@ constexpr int kWave = 64;
 enum State { COUNTS_VALID = 1, ALIAS_VALID = 2, SWEPT = 3 };
 
 // One rebuild work item: a slice [p0, p1) of word w's word-major segment.
+// Mixture tables are launched by size class so that a small table does not reserve a large
+// table's LDS: list capacity of each class, 0 = the largest that fits LDS, -1 = any size (built
+// in the global workspace).
+constexpr int kMixClasses = 8;
+constexpr int32_t kMixClassCap[kMixClasses] = {64, 256, 1024, 2048, 4096, 8192, 0, -1};
+
 struct RebuildTile {
     int32_t w;
     int32_t p0;
@@ -106,9 +112,10 @@ struct lda_ctx {
     int32_t* d_dense_alias_words = nullptr;  // words that draw from a dense K-bin table
     int32_t n_dense_alias = 0;
     int32_t n_mix = 0;                   // words that draw from the mixture
-    // the mixture words by list capacity: <= 64, <= 512, <= 4096, <= LDS maximum, larger
-    int32_t* d_mix_class[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
-    int32_t n_mix_class[5] = {0, 0, 0, 0, 0};
+    // the mixture words by list capacity (kMixClassCap; the last class is built in the global
+    // workspace)
+    int32_t* d_mix_class[lda::kMixClasses] = {};
+    int32_t n_mix_class[lda::kMixClasses] = {};
     int32_t* d_sparse_words = nullptr;   // words with a sparse row (subset of the mixture words)
     int32_t n_sparse = 0;
     int32_t* d_compact_words = nullptr;  // mixture words with a dense row (list made by compaction)
