@@ -245,7 +245,7 @@ def main():
     }
     g.close()
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 3000, "c3": 300000}[args.workload]
+        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 60000, "c3": 600000}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample,
                                            hybrid.get("dense_alias_min_count", 0))
     print(json.dumps(out))
