@@ -178,6 +178,9 @@ int launch_loglik_word_hybrid(lda_ctx* c, double* word_part);
 int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries);
 int max_lds_table_entries();  // largest alias table built in LDS
 
+// Up to this many topics the doc pass keeps a copy of n_k in every workgroup's LDS.
+constexpr int32_t kNkLdsTopics = 16384;
+
 // slot of topic t in a hash row of 2^lg slots (multiplicative hashing, top bits)
 __host__ __device__ inline uint32_t row_hash_slot(int32_t t, uint32_t lg)
 {
