@@ -57,6 +57,9 @@ void free_all(lda_ctx* c)
     dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
     dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
     dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces);
+    dev_free(c->d_sort_keys);
+    if (c->d_sort_tmp) (void)hipFree(c->d_sort_tmp);
+    c->d_sort_tmp = nullptr;
     for (hipEvent_t& e : c->pass_ev) {
         if (e) (void)hipEventDestroy(e);
         e = nullptr;

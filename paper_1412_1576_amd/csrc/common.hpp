@@ -148,6 +148,9 @@ struct lda_ctx {
     std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table
     std::vector<uint32_t> h_sp_off, h_hs_off;
     // scratch
+    int32_t* d_sort_keys = nullptr;    // [N] sorted copy of z (n_k by sorting, very large K)
+    void* d_sort_tmp = nullptr;
+    size_t sort_tmp_bytes = 0;
     double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
     int32_t n_partial = 0;
     int32_t* d_row = nullptr;          // [max(K,1)] row staging for accessors
@@ -212,6 +215,7 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sweep_split(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
+int launch_nk_by_sort(lda_ctx* c);  // n_k from a radix sort of z (K too large for LDS histograms)
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
 int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
 int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo, int32_t hi,

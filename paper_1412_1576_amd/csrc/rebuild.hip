@@ -6,7 +6,8 @@
 // then histograms a tile of a segment in LDS and writes the dense row.  Words whose segment is longer than one tile are split
 // over several workgroups whose partial histograms are merged into a
 // pre-zeroed row with integer atomics (order-free, hence exact).
-// n_k: an LDS-privatised histogram of z over all tokens.
+// n_k: an LDS-privatised histogram of z over all tokens (a radix sort of z for very large K,
+// layout.hip).
 #include "common.hpp"
 
 namespace lda {
@@ -254,16 +255,6 @@ __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __r
     }
 }
 
-// n_k for very large K: one global atomic per token (more topic ranges than this is
-// worth would each re-read all of z)
-__global__ __launch_bounds__(256) void nk_atomic_kernel(const int32_t* __restrict__ z, int64_t N,
-                                                        int32_t* __restrict__ nk)
-{
-    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < N;
-         g += (int64_t)gridDim.x * blockDim.x)
-        atomicAdd(&nk[z[g]], 1);
-}
-
 // hash row of word w from its list: clear, then insert every (topic, count)
 __device__ __forceinline__ void fill_hash_row(uint2* __restrict__ hs, uint32_t lg,
                                               const int32_t* __restrict__ topic,
@@ -473,6 +464,7 @@ int launch_rebuild_hybrid(lda_ctx* c)
         LDA_HIP(c, hipGetLastError());
     }
     // ---- n_k ----
+    if (K > 8 * 32768) return launch_nk_by_sort(c);
     hipLaunchKernelGGL(fill_i32_kernel, dim3(64), dim3(256), 0, c->stream, c->d_nk, (int64_t)K, 0);
     LDA_HIP(c, hipGetLastError());
     int64_t blocks = (c->N + 65535) / 65536;
@@ -486,9 +478,6 @@ int launch_rebuild_hybrid(lda_ctx* c)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(nk_hist_kernel, dim3((unsigned)blocks), dim3(1024), lds, c->stream,
                            c->d_z, c->N, K, c->d_nk);
-    } else if (K > 8 * span) {
-        hipLaunchKernelGGL(nk_atomic_kernel, dim3(8192), dim3(256), 0, c->stream, c->d_z, c->N,
-                           c->d_nk);
     } else {
         const size_t lds = sizeof(int32_t) * (size_t)span;
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_ranges_kernel),
