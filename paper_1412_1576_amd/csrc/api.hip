@@ -58,6 +58,10 @@ void free_all(lda_ctx* c)
     dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
     dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces);
     dev_free(c->d_sort_keys);
+    dev_free(c->d_sp_wloc); dev_free(c->d_sp_keys); dev_free(c->d_sp_sorted); dev_free(c->d_sp_runlen);
+    dev_free(c->d_sp_first); dev_free(c->d_sp_nruns);
+    if (c->d_sp_tmp) (void)hipFree(c->d_sp_tmp);
+    c->d_sp_tmp = nullptr;
     if (c->d_sort_tmp) (void)hipFree(c->d_sort_tmp);
     c->d_sort_tmp = nullptr;
     for (hipEvent_t& e : c->pass_ev) {
@@ -70,12 +74,10 @@ void free_all(lda_ctx* c)
     dev_free(c->d_flag);
     dev_free(c->d_dense_alias_words);
     for (int i = 0; i < kMixClasses; ++i) dev_free(c->d_mix_class[i]);
-    for (int i = 0; i < 4; ++i) dev_free(c->d_sortsp_class[i]);
     dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
     dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
     dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); c->d_metaB = nullptr;
     dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
-    dev_free(c->d_scratch_rows); dev_free(c->d_bigsp_words);
 }
 
 template <class T>
@@ -109,9 +111,8 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->h_wkind.resize(V);
     c->h_sp_off.assign((size_t)V + 1, 0);
     c->h_hs_off.assign((size_t)V + 1, 0);
-    std::vector<int32_t> dense_alias, mix, sparse, compact, bigsp, mixc[kMixClasses], sortc[4];
+    std::vector<int32_t> dense_alias, mix, sparse, compact, mixc[kMixClasses];
     std::vector<uint4> meta(2 * (size_t)V, make_uint4(0u, 0u, 0u, 0u));
-    static const int32_t sort_cap[4] = {64, 512, 4096, 16384};
     const int32_t lds_max = max_lds_table_entries();
     uint64_t list_total = 0, hash_total = 0;
     for (int32_t w = 0; w < V; ++w) {
@@ -149,19 +150,13 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
                 while (hcap < 2u * (uint32_t)cap) hcap <<= 1;
                 while ((1u << lg) < hcap) ++lg;
                 hash_total += hcap;
-                if (cw <= sort_cap[3]) {
-                    int sc = 3;
-                    for (int i = 0; i < 4; ++i) if (cw <= sort_cap[i]) { sc = i; break; }
-                    sortc[sc].push_back(w);
-                } else {
-                    bigsp.push_back(w);
-                }
             }
         }
         meta[2 * (size_t)w + 1] = make_uint4(c->h_sp_off[w], c->h_hs_off[w], lg, kind);
         if (list_total > 0x7FFFFFFFull || hash_total > 0xFFFFFFFFull)
             return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: sparse rows exceed 2^31 entries");
     }
+    c->h_sparse_p0 = woff[H];
     c->h_sp_off[V] = (uint32_t)list_total;
     c->h_hs_off[V] = (uint32_t)hash_total;
     c->total_list = (int64_t)list_total;
@@ -170,7 +165,6 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->n_mix = (int32_t)mix.size();
     c->n_sparse = (int32_t)sparse.size();
     c->n_compact = (int32_t)compact.size();
-    c->n_bigsp = (int32_t)bigsp.size();
     if (c->n_dense_alias > 0 && K > lds_max && (double)H * (double)K > 4.0e9)
         return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: dense tables for %d words at K = %d", H, K);
 
@@ -179,14 +173,9 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     UP(d_dense_alias_words, dense_alias, "dense-table words");
     UP(d_sparse_words, sparse, "sparse-row words");
     UP(d_compact_words, compact, "compaction words");
-    UP(d_bigsp_words, bigsp, "big sparse words");
     for (int i = 0; i < kMixClasses; ++i) {
         c->n_mix_class[i] = (int32_t)mixc[i].size();
         UP(d_mix_class[i], mixc[i], "mixture class");
-    }
-    for (int i = 0; i < 4; ++i) {
-        c->n_sortsp_class[i] = (int32_t)sortc[i].size();
-        UP(d_sortsp_class[i], sortc[i], "sort class");
     }
     UP(d_sp_off, c->h_sp_off, "list offsets");
     UP(d_hs_off, c->h_hs_off, "hash offsets");
@@ -210,13 +199,6 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
         int64_t wg = (int64_t)(2.0e9 / (double)c->big_ws_stride);
         c->n_big_wg = (int32_t)std::max<int64_t>(1, std::min<int64_t>(256, wg));
         AL(d_big_ws, c->big_ws_stride * (size_t)c->n_big_wg, "table workspace");
-    }
-    if (c->n_bigsp > 0) {
-        int64_t rows = (int64_t)(1.0e9 / (4.0 * (double)K));
-        c->n_scratch_rows = (int32_t)std::max<int64_t>(1, std::min<int64_t>(256, rows));
-        AL(d_scratch_rows, (size_t)c->n_scratch_rows * (size_t)K, "scratch rows");
-        LDA_HIP(c, hipMemsetAsync(c->d_scratch_rows, 0,
-                                  sizeof(int32_t) * (size_t)c->n_scratch_rows * (size_t)K, c->stream));
     }
 #undef AL
     return LDA_OK;

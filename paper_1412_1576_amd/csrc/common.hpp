@@ -136,18 +136,22 @@ struct lda_ctx {
     unsigned char* d_big_ws = nullptr;   // list memory of the workgroups that build big tables
     size_t big_ws_stride = 0;
     int32_t n_big_wg = 0;
-    int32_t* d_scratch_rows = nullptr;   // dense scratch rows for the rebuild of big sparse words
-    int32_t n_scratch_rows = 0;
-    int32_t* d_bigsp_words = nullptr;    // sparse-row words rebuilt through scratch rows
-    int32_t n_bigsp = 0;
-    // sparse-row words rebuilt by an LDS sort, by token count: <= 64, <= 512, <= 4096, <= 16384
-    int32_t* d_sortsp_class[4] = {nullptr, nullptr, nullptr, nullptr};
-    int32_t n_sortsp_class[4] = {0, 0, 0, 0};
     int64_t total_list = 0, total_hash = 0;
     std::vector<int32_t> h_wcount;       // corpus frequency of every word
     std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table
     std::vector<uint32_t> h_sp_off, h_hs_off;
     // scratch
+    // sparse rows by one global sort (layout.hip): word index of every sparse-row token, keys,
+    // sorted keys, run lengths, first run of every word, number of runs
+    uint32_t* d_sp_wloc = nullptr;
+    uint64_t* d_sp_keys = nullptr;
+    uint64_t* d_sp_sorted = nullptr;
+    uint32_t* d_sp_runlen = nullptr;
+    int32_t* d_sp_first = nullptr;
+    int32_t* d_sp_nruns = nullptr;
+    void* d_sp_tmp = nullptr;
+    size_t sp_tmp_bytes = 0;
+    int64_t h_sparse_p0 = 0;           // word-major position of the first sparse-row token
     int32_t* d_sort_keys = nullptr;    // [N] sorted copy of z (n_k by sorting, very large K)
     void* d_sort_tmp = nullptr;
     size_t sort_tmp_bytes = 0;
@@ -215,7 +219,8 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sweep_split(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
-int launch_nk_by_sort(lda_ctx* c);  // n_k from a radix sort of z (K too large for LDS histograms)
+int launch_nk_by_sort(lda_ctx* c);
+int launch_sparse_lists_by_sort(lda_ctx* c);  // lists of the sparse-row words; first runs in d_sp_first  // n_k from a radix sort of z (K too large for LDS histograms)
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
 int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
 int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo, int32_t hi,

@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_run_length_encode.hpp>
 
 #include "common.hpp"
 
@@ -89,6 +90,110 @@ __global__ __launch_bounds__(256) void nk_from_sorted_kernel(const int32_t* __re
     nk[k] = (int32_t)(bound[1] - bound[0]);
 }
 
+// ---- sparse rows by one global sort (words without a dense row are the ids >= H, so their
+// tokens are the word-major positions [p0, N)) ---------------------------------------------
+
+// wloc[i] = (word of position p0 + i) - H: the last w >= H with woff[w] <= p0 + i
+__global__ __launch_bounds__(256) void sparse_wloc_kernel(const int32_t* __restrict__ woff, int32_t H,
+                                                          int32_t V, int64_t p0, int64_t n,
+                                                          uint32_t* __restrict__ wloc)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t p = p0 + i;
+        int32_t lo = H, hi = V;  // woff[lo] <= p < woff[hi]
+        while (hi - lo > 1) {
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            if (woff[mid] <= p) lo = mid; else hi = mid;
+        }
+        wloc[i] = (uint32_t)(lo - H);
+    }
+}
+
+// key = (word - H) << tb | topic
+__global__ __launch_bounds__(256) void sparse_keys_kernel(const int32_t* __restrict__ zt, int32_t sh,
+                                                          uint32_t zmask,
+                                                          const uint32_t* __restrict__ wloc,
+                                                          int64_t p0, int64_t n, int32_t tb,
+                                                          uint64_t* __restrict__ keys)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        keys[i] = ((uint64_t)wloc[i] << tb) | (uint64_t)((uint32_t)zt[(size_t)(p0 + i) << sh] & zmask);
+}
+
+// first[wl] = index of the first run (distinct key) of word H + wl, wl = 0..n_words
+__global__ __launch_bounds__(256) void sparse_first_run_kernel(const uint64_t* __restrict__ uniq,
+                                                               const int32_t* __restrict__ n_runs,
+                                                               int32_t n_words, int32_t tb,
+                                                               int32_t* __restrict__ first)
+{
+    const int32_t wl = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (wl > n_words) return;
+    const uint64_t key = (uint64_t)wl << tb;
+    int32_t lo = 0, hi = *n_runs;
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        if (uniq[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    first[wl] = lo;
+}
+
+// run r is entry r - first[word] of its word's list; it also goes into the word's hash row
+// (cleared beforehand), one thread per entry so that a word with a million entries is
+// filled by as many threads
+__global__ __launch_bounds__(256) void sparse_lists_kernel(const uint64_t* __restrict__ uniq,
+                                                           const uint32_t* __restrict__ counts,
+                                                           const int32_t* __restrict__ n_runs,
+                                                           const int32_t* __restrict__ first,
+                                                           int32_t tb, int32_t H,
+                                                           const uint32_t* __restrict__ sp_off,
+                                                           int32_t* __restrict__ sp_topic,
+                                                           int32_t* __restrict__ sp_count,
+                                                           const uint32_t* __restrict__ hs_off,
+                                                           uint2* __restrict__ hs)
+{
+    const int64_t nr = *n_runs;
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < nr;
+         r += (int64_t)gridDim.x * blockDim.x) {
+        const uint64_t key = uniq[r];
+        const uint32_t wl = (uint32_t)(key >> tb);
+        const int32_t w = H + (int32_t)wl;
+        const int32_t topic = (int32_t)(key & ((1ull << tb) - 1ull));
+        const uint32_t count = counts[r];
+        const size_t pos = (size_t)sp_off[w] + (size_t)(r - first[wl]);
+        sp_topic[pos] = topic;
+        sp_count[pos] = (int32_t)count;
+        uint2* __restrict__ row = hs + hs_off[w];
+        const uint32_t cap = hs_off[w + 1] - hs_off[w];  // a power of two, at least twice the entries
+        const uint32_t lg = 31u - (uint32_t)__clz((int)cap);
+        uint32_t slot = row_hash_slot(topic, lg);
+        for (uint32_t i = 0; i < cap; ++i) {
+            if (atomicCAS(&row[slot].x, 0xFFFFFFFFu, (uint32_t)topic) == 0xFFFFFFFFu) {
+                row[slot].y = count;
+                break;
+            }
+            slot = (slot + 1) & (cap - 1);
+        }
+    }
+}
+
+// list lengths from the first-run indices
+__global__ __launch_bounds__(256) void sparse_nnz_kernel(const int32_t* __restrict__ first,
+                                                         int32_t n_words, int32_t H,
+                                                         int32_t* __restrict__ sp_nnz)
+{
+    const int32_t wl = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (wl < n_words) sp_nnz[H + wl] = first[wl + 1] - first[wl];
+}
+
+__global__ __launch_bounds__(256) void clear_hash_kernel(uint2* __restrict__ hs, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        hs[i] = make_uint2(0xFFFFFFFFu, 0u);
+}
+
 unsigned grid_for(int64_t n, int block, unsigned cap = 8192)
 {
     int64_t b = (n + block - 1) / block;
@@ -135,6 +240,70 @@ int launch_nk_by_sort(lda_ctx* c)
     hipLaunchKernelGGL(nk_from_sorted_kernel, dim3((c->K + 255) / 256), dim3(256), 0, c->stream,
                        c->d_sort_keys, N, c->K, c->d_nk);
     LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
+
+// Sorted (topic, count) lists, their lengths and the hash rows of every word without a dense
+// row, from one radix sort of (word, topic) keys over their tokens and a run-length encoding.
+int launch_sparse_lists_by_sort(lda_ctx* c)
+{
+    const int32_t H = c->H, V = c->V, n_words = V - H;
+    const int64_t p0 = c->h_sparse_p0, n = c->N - p0;
+    if (n_words <= 0) return LDA_OK;
+    int tb = 1, wb = 1;
+    while (tb < 31 && (1LL << tb) < (long long)c->K) ++tb;
+    while (wb < 31 && (1LL << wb) < (long long)n_words) ++wb;
+    if (!c->d_sp_first) {
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_first), sizeof(int32_t) * ((size_t)n_words + 2)));
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_nruns), sizeof(int32_t) * 2));
+        LDA_HIP(c, hipMemsetAsync(c->d_sp_nruns, 0, sizeof(int32_t) * 2, c->stream));
+        const size_t m = (size_t)(n > 0 ? n : 1);
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_wloc), sizeof(uint32_t) * m));
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_keys), sizeof(uint64_t) * m));
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_sorted), sizeof(uint64_t) * m));
+        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_runlen), sizeof(uint32_t) * m));
+        size_t b1 = 0, b2 = 0;
+        LDA_HIP(c, rocprim::radix_sort_keys(nullptr, b1, c->d_sp_keys, c->d_sp_sorted, (size_t)n, 0u,
+                                            (unsigned)(tb + wb), c->stream));
+        LDA_HIP(c, rocprim::run_length_encode(nullptr, b2, c->d_sp_sorted, (size_t)n, c->d_sp_keys,
+                                              c->d_sp_runlen, c->d_sp_nruns, c->stream));
+        c->sp_tmp_bytes = b1 > b2 ? b1 : b2;
+        LDA_HIP(c, hipMalloc(&c->d_sp_tmp, c->sp_tmp_bytes ? c->sp_tmp_bytes : 1));
+        if (n > 0) {
+            hipLaunchKernelGGL(sparse_wloc_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream,
+                               c->d_woff, H, V, p0, n, c->d_sp_wloc);
+            LDA_HIP(c, hipGetLastError());
+        }
+    }
+    if (n > 0) {
+        hipLaunchKernelGGL(sparse_keys_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream, c->d_zt,
+                           c->zt_shift, c->zt_mask, c->d_sp_wloc, p0, n, tb, c->d_sp_keys);
+        LDA_HIP(c, hipGetLastError());
+        size_t bytes = c->sp_tmp_bytes;
+        LDA_HIP(c, rocprim::radix_sort_keys(c->d_sp_tmp, bytes, c->d_sp_keys, c->d_sp_sorted, (size_t)n,
+                                            0u, (unsigned)(tb + wb), c->stream));
+        bytes = c->sp_tmp_bytes;
+        // the distinct keys overwrite the unsorted ones
+        LDA_HIP(c, rocprim::run_length_encode(c->d_sp_tmp, bytes, c->d_sp_sorted, (size_t)n,
+                                              c->d_sp_keys, c->d_sp_runlen, c->d_sp_nruns, c->stream));
+    }
+    hipLaunchKernelGGL(sparse_first_run_kernel, dim3((n_words + 1 + 255) / 256), dim3(256), 0, c->stream,
+                       c->d_sp_keys, c->d_sp_nruns, n_words, tb, c->d_sp_first);
+    LDA_HIP(c, hipGetLastError());
+    hipLaunchKernelGGL(sparse_nnz_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c->stream,
+                       c->d_sp_first, n_words, H, c->d_sp_nnz);
+    LDA_HIP(c, hipGetLastError());
+    if (c->total_hash > 0) {
+        hipLaunchKernelGGL(clear_hash_kernel, dim3(grid_for(c->total_hash, 256, 65536)), dim3(256), 0,
+                           c->stream, c->d_hs, c->total_hash);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (n > 0) {
+        hipLaunchKernelGGL(sparse_lists_kernel, dim3(grid_for(n, 256, 65536)), dim3(256), 0, c->stream,
+                           c->d_sp_keys, c->d_sp_runlen, c->d_sp_nruns, c->d_sp_first, tb, H, c->d_sp_off,
+                           c->d_sp_topic, c->d_sp_count, c->d_hs_off, c->d_hs);
+        LDA_HIP(c, hipGetLastError());
+    }
     return LDA_OK;
 }
 

@@ -228,7 +228,6 @@ namespace lda {
 
 namespace {
 
-constexpr int32_t kSortPad = 0x7FFFFFFF;
 
 // n_k for K beyond one LDS histogram: blockIdx.y selects a range of `span` topics
 __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __restrict__ z,
@@ -255,174 +254,6 @@ __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __r
     }
 }
 
-// hash row of word w from its list: clear, then insert every (topic, count)
-__device__ __forceinline__ void fill_hash_row(uint2* __restrict__ hs, uint32_t lg,
-                                              const int32_t* __restrict__ topic,
-                                              const int32_t* __restrict__ count, int32_t nnz)
-{
-    const uint32_t cap = 1u << lg;
-    for (uint32_t i = threadIdx.x; i < cap; i += blockDim.x) hs[i] = make_uint2(0xFFFFFFFFu, 0u);
-    __syncthreads();
-    for (int32_t i = threadIdx.x; i < nnz; i += blockDim.x) {
-        // the list was written by this workgroup a moment ago: read it past the L1
-        const int32_t t = __hip_atomic_load(&topic[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int32_t v = __hip_atomic_load(&count[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        uint32_t s = row_hash_slot(t, lg);
-        for (uint32_t n = 0; n < cap; ++n) {
-            const uint32_t prev = atomicCAS(&hs[s].x, 0xFFFFFFFFu, (uint32_t)t);
-            if (prev == 0xFFFFFFFFu) {
-                hs[s].y = (uint32_t)v;
-                break;
-            }
-            s = (s + 1) & (cap - 1);
-        }
-    }
-}
-
-__device__ __forceinline__ uint32_t log2_pow2(uint32_t x) { return 31u - (uint32_t)__clz((int)x); }
-
-// One workgroup per word with at most P tokens (P a power of two = LDS capacity):
-// gather the word's topics, bitonic sort in LDS, run-length encode into the list,
-// fill the hash row.
-__global__ __launch_bounds__(1024) void sparse_rows_sort_kernel(
-    const int32_t* __restrict__ words, int32_t P, const int32_t* __restrict__ woff,
-    const int32_t* __restrict__ zw, int32_t sh, uint32_t zmask,
-    const uint32_t* __restrict__ sp_off, int32_t* __restrict__ sp_topic,
-    int32_t* __restrict__ sp_count, int32_t* __restrict__ sp_nnz,
-    const uint32_t* __restrict__ hs_off, uint2* __restrict__ hs)
-{
-    extern __shared__ int32_t sm[];
-    int32_t* key = sm;        // [P]
-    int32_t* head = sm + P;   // [P + 1] start position of every run
-    __shared__ uint32_t wcnt[16];
-    const int32_t w = words[blockIdx.x];
-    const int32_t p0 = woff[w], c = woff[w + 1] - p0;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int lane = tid & (kWave - 1), wv = tid >> 6, nw = nt >> 6;
-    if (c == 0) {
-        if (tid == 0) sp_nnz[w] = 0;
-        return;
-    }
-    int32_t Q = 2;  // sort size: smallest power of two >= c
-    while (Q < c) Q <<= 1;
-    for (int32_t i = tid; i < Q; i += nt) key[i] = (i < c) ? (int32_t)((uint32_t)zw[(size_t)(p0 + i) << sh] & zmask) : kSortPad;
-    __syncthreads();
-    for (int32_t k = 2; k <= Q; k <<= 1) {
-        for (int32_t j = k >> 1; j > 0; j >>= 1) {
-            for (int32_t i = tid; i < Q; i += nt) {
-                const int32_t ixj = i ^ j;
-                if (ixj > i) {
-                    const int32_t a = key[i], b = key[ixj];
-                    const bool up = (i & k) == 0;
-                    if ((a > b) == up) {
-                        key[i] = b;
-                        key[ixj] = a;
-                    }
-                }
-            }
-            __syncthreads();
-        }
-    }
-    // run heads, in order
-    const size_t off = sp_off[w];
-    uint32_t base = 0;
-    for (int32_t i0 = 0; i0 < c; i0 += nt) {
-        const int32_t i = i0 + tid;
-        const bool is_head = (i < c) && (i == 0 || key[i] != key[i - 1]);
-        const uint64_t mask = __ballot(is_head);
-        __syncthreads();
-        if (lane == 0) wcnt[wv] = (uint32_t)__popcll(mask);
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-        for (int q = 0; q < nw; ++q) {
-            if (q < wv) before += wcnt[q];
-            total += wcnt[q];
-        }
-        if (is_head) {
-            const uint32_t r = base + before + (uint32_t)__builtin_amdgcn_mbcnt_hi(
-                (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            head[r] = i;
-            sp_topic[off + r] = key[i];
-        }
-        base += total;
-    }
-    const int32_t nnz = (int32_t)base;
-    if (tid == 0) {
-        head[nnz] = c;
-        sp_nnz[w] = nnz;
-    }
-    __syncthreads();
-    for (int32_t r = tid; r < nnz; r += nt) sp_count[off + r] = head[r + 1] - head[r];
-    __syncthreads();
-    const uint32_t hcap = hs_off[w + 1] - hs_off[w];
-    fill_hash_row(hs + hs_off[w], log2_pow2(hcap), sp_topic + off, sp_count + off, nnz);
-}
-
-// big sparse words, step 1: histogram the word's tokens into its scratch row
-__global__ __launch_bounds__(256) void scratch_hist_kernel(const int32_t* __restrict__ words,
-                                                           int32_t n_words, int32_t tile,
-                                                           const int32_t* __restrict__ woff,
-                                                           const int32_t* __restrict__ zw,
-                                                           int32_t sh, uint32_t zmask, int32_t K,
-                                                           int32_t* __restrict__ scratch)
-{
-    const int32_t wi = blockIdx.y;
-    if (wi >= n_words) return;
-    const int32_t w = words[wi];
-    const int32_t p0 = woff[w], p1 = woff[w + 1];
-    int32_t* __restrict__ row = scratch + (size_t)wi * (size_t)K;
-    for (int32_t b = p0 + (int32_t)blockIdx.x * tile; b < p1; b += (int32_t)gridDim.x * tile) {
-        const int32_t e = (b + tile < p1) ? b + tile : p1;
-        for (int32_t p = b + (int32_t)threadIdx.x; p < e; p += (int32_t)blockDim.x)
-            atomicAdd(&row[(uint32_t)zw[(size_t)p << sh] & zmask], 1);
-    }
-}
-
-// big sparse words, step 2: compact the scratch row into the list, clear it, fill the hash row
-__global__ __launch_bounds__(1024) void scratch_compact_kernel(
-    const int32_t* __restrict__ words, int32_t K, int32_t* __restrict__ scratch,
-    const uint32_t* __restrict__ sp_off, int32_t* __restrict__ sp_topic,
-    int32_t* __restrict__ sp_count, int32_t* __restrict__ sp_nnz,
-    const uint32_t* __restrict__ hs_off, uint2* __restrict__ hs)
-{
-    __shared__ uint32_t wcnt[16];
-    const int32_t w = words[blockIdx.x];
-    int32_t* __restrict__ row = scratch + (size_t)blockIdx.x * (size_t)K;
-    const size_t off = sp_off[w];
-    const int tid = threadIdx.x, nt = blockDim.x;
-    const int lane = tid & (kWave - 1), wv = tid >> 6, nw = nt >> 6;
-    uint32_t base = 0;
-    for (int32_t k0 = 0; k0 < K; k0 += nt) {
-        const int32_t k = k0 + tid;
-        int32_t v = 0;
-        if (k < K) {
-            v = row[k];
-            if (v) row[k] = 0;  // leave the scratch row clean for the next batch
-        }
-        const uint64_t mask = __ballot(v > 0);
-        __syncthreads();
-        if (lane == 0) wcnt[wv] = (uint32_t)__popcll(mask);
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-        for (int q = 0; q < nw; ++q) {
-            if (q < wv) before += wcnt[q];
-            total += wcnt[q];
-        }
-        if (v > 0) {
-            const size_t p = off + base + before + (uint32_t)__builtin_amdgcn_mbcnt_hi(
-                (uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-            sp_topic[p] = k;
-            sp_count[p] = v;
-        }
-        base += total;
-    }
-    const int32_t nnz = (int32_t)base;
-    if (tid == 0) sp_nnz[w] = nnz;
-    __syncthreads();
-    const uint32_t hcap = hs_off[w + 1] - hs_off[w];
-    fill_hash_row(hs + hs_off[w], log2_pow2(hcap), sp_topic + off, sp_count + off, nnz);
-}
-
 }  // namespace
 
 int launch_rebuild_hybrid(lda_ctx* c)
@@ -433,35 +264,10 @@ int launch_rebuild_hybrid(lda_ctx* c)
         const int rc = launch_dense_rows_hybrid(c);
         if (rc != LDA_OK) return rc;
     }
-    // ---- sparse rows: LDS sort classes ----
-    static const int32_t kSortCap[4] = {64, 512, 4096, 16384};
-    for (int cl = 0; cl < 4; ++cl) {
-        if (c->n_sortsp_class[cl] == 0) continue;
-        const int32_t P = kSortCap[cl];
-        const size_t lds = sizeof(int32_t) * (2 * (size_t)P + 1);
-        if (lds > 48 * 1024)
-            LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(sparse_rows_sort_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        const int threads = P <= 64 ? 64 : (P <= 512 ? 256 : 1024);
-        hipLaunchKernelGGL(sparse_rows_sort_kernel, dim3(c->n_sortsp_class[cl]), dim3(threads), lds,
-                           c->stream, c->d_sortsp_class[cl], P, c->d_woff, c->d_zt, c->zt_shift,
-                           c->zt_mask,
-                           c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz, c->d_hs_off,
-                           c->d_hs);
-        LDA_HIP(c, hipGetLastError());
-    }
-    // ---- sparse rows: big words through dense scratch rows, a batch at a time ----
-    for (int32_t b0 = 0; b0 < c->n_bigsp; b0 += c->n_scratch_rows) {
-        const int32_t nb = std::min(c->n_scratch_rows, c->n_bigsp - b0);
-        hipLaunchKernelGGL(scratch_hist_kernel, dim3(64, nb), dim3(256), 0, c->stream,
-                           c->d_bigsp_words + b0, nb, 4096, c->d_woff, c->d_zt, c->zt_shift, c->zt_mask,
-                           K,
-                           c->d_scratch_rows);
-        LDA_HIP(c, hipGetLastError());
-        hipLaunchKernelGGL(scratch_compact_kernel, dim3(nb), dim3(1024), 0, c->stream,
-                           c->d_bigsp_words + b0, K, c->d_scratch_rows, c->d_sp_off, c->d_sp_topic,
-                           c->d_sp_count, c->d_sp_nnz, c->d_hs_off, c->d_hs);
-        LDA_HIP(c, hipGetLastError());
+    // ---- sparse rows: lists, lengths and hash rows by one global sort (layout.hip) ----
+    if (c->V > c->H) {
+        const int rc = launch_sparse_lists_by_sort(c);
+        if (rc != LDA_OK) return rc;
     }
     // ---- n_k ----
     if (K > 8 * 32768) return launch_nk_by_sort(c);
