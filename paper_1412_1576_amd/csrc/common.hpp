@@ -92,6 +92,13 @@ struct lda_ctx {
     uint8_t* d_tokdoc = nullptr;     // [N] index of the token's document inside its tile
     int32_t n_chunks = 0;
     int32_t chunk_tokens = 0, chunk_docs = 0, sweep_block = 0;
+    // second tiling of the same documents with larger tiles, used by the doc pass of chains
+    // of at most two steps (n_chunks2 == 0: not built).  A document is "long" under both
+    // tilings when it exceeds chunk_tokens.
+    int32_t* d_chunk_doc2 = nullptr;
+    uint8_t* d_tokdoc2 = nullptr;
+    int32_t n_chunks2 = 0;
+    int32_t chunk_tokens2 = 0, chunk_docs2 = 0, sweep_block2 = 0;
     // documents too long for an LDS tile: hashed in a global workspace
     int32_t* d_long_doc = nullptr;     // [n_long] document ids
     int64_t* d_long_slot = nullptr;    // [n_long+1] first hash slot of each long document

@@ -412,6 +412,11 @@ int launch_tokdoc(lda_ctx* c)
                            c->d_chunk_doc, c->chunk_tokens, c->d_tokdoc);
         LDA_HIP(c, hipGetLastError());
     }
+    if (c->n_chunks2 > 0) {
+        hipLaunchKernelGGL(tokdoc_kernel, dim3(c->n_chunks2), dim3(256), 0, c->stream, c->d_doff,
+                           c->d_chunk_doc2, c->chunk_tokens2, c->d_tokdoc2);
+        LDA_HIP(c, hipGetLastError());
+    }
     return LDA_OK;
 }
 

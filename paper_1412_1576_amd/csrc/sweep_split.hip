@@ -120,6 +120,8 @@ struct SplitArgs {
     const int4* pieces;
     int32_t n_chunks, n_row_items, n_pieces;
     int32_t K, cap_tokens;
+    int32_t max_doc_tokens;  // a longer document is a tile of its own, left to the long-document kernel
+    int32_t doc_block;       // threads per workgroup of the doc pass
     int32_t tile_lds_ints;  // ints of a document tile in LDS (the n_k copy follows it)
     double alpha, beta, alphabar, betabar;
     uint32_t seed_lo, seed_hi, sweep;
@@ -635,7 +637,7 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && NW + ND <= 2) ? (MAXB <= 256 ? 7 :
     if (c >= A.n_chunks) return;
     const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
     const int32_t ntok = A.doff[d1] - A.doff[d0];
-    if (ntok > A.cap_tokens || ntok == 0) return;  // a long document (other kernel) / nothing
+    if (ntok == 0 || (d1 - d0 == 1 && ntok > A.max_doc_tokens)) return;  // nothing / a long document
     // the word-pass records do not depend on the tile: their gather (one random line per
     // token) is issued first and overlaps the staging of the documents
     const int32_t tok0 = A.doff[d0];
@@ -797,7 +799,7 @@ int launch_doc_tiles_as(lda_ctx* c, const SplitArgs& A, size_t lds)
     auto kern = doc_pass_tiles_kernel<NW, ND, T, MAXB, NKL>;
     const int rc = raise_lds_limit(c, kern, lds);
     if (rc != LDA_OK) return rc;
-    hipLaunchKernelGGL(kern, dim3(xcd_grid(c->n_chunks)), dim3(c->sweep_block), lds, c->stream, A);
+    hipLaunchKernelGGL(kern, dim3(xcd_grid(A.n_chunks)), dim3(A.doc_block), lds, c->stream, A);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }
@@ -807,17 +809,17 @@ int launch_doc_tiles(lda_ctx* c, const SplitArgs& A, size_t lds)
 {
     if (c->K <= kNkLdsTopics) {  // with the workgroup's own copy of n_k
         lds += sizeof(int32_t) * (size_t)c->K;
-        if (c->sweep_block <= 256) return launch_doc_tiles_as<NW, ND, T, 256, true>(c, A, lds);
-        if (c->sweep_block <= 768) return launch_doc_tiles_as<NW, ND, T, 768, true>(c, A, lds);
+        if (A.doc_block <= 256) return launch_doc_tiles_as<NW, ND, T, 256, true>(c, A, lds);
+        if (A.doc_block <= 768) return launch_doc_tiles_as<NW, ND, T, 768, true>(c, A, lds);
         return launch_doc_tiles_as<NW, ND, T, 1024, true>(c, A, lds);
     }
-    if (c->sweep_block <= 256) return launch_doc_tiles_as<NW, ND, T, 256, false>(c, A, lds);
+    if (A.doc_block <= 256) return launch_doc_tiles_as<NW, ND, T, 256, false>(c, A, lds);
     return launch_doc_tiles_as<NW, ND, T, 1024, false>(c, A, lds);
 }
 
-int tokens_per_thread(const lda_ctx* c)
+int tokens_per_thread(const SplitArgs& A)
 {
-    return (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block;
+    return (A.cap_tokens + A.doc_block - 1) / A.doc_block;
 }
 
 template <int NW, int ND>
@@ -831,7 +833,7 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
         LDA_HIP(c, hipEventRecord(c->pass_ev[0], c->stream));
     }
     if (need_proposals) {
-        hipLaunchKernelGGL((doc_proposals_kernel<NW, ND>), dim3(xcd_grid(c->n_chunks)), dim3(256), 0,
+        hipLaunchKernelGGL((doc_proposals_kernel<NW, ND>), dim3(xcd_grid(A.n_chunks)), dim3(256), 0,
                            c->stream, A);
         LDA_HIP(c, hipGetLastError());
     }
@@ -860,9 +862,9 @@ int launch_chain(lda_ctx* c, const SplitArgs& A, bool need_proposals)
         LDA_HIP(c, hipGetLastError());
     }
     if (timed) LDA_HIP(c, hipEventRecord(c->pass_ev[1], c->stream));
-    if (c->n_chunks > 0) {
-        const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
-        const int tpt = tokens_per_thread(c);
+    if (A.n_chunks > 0) {
+        const size_t lds = sizeof(int32_t) * (size_t)A.tile_lds_ints;
+        const int tpt = tokens_per_thread(A);
         rc = tpt <= 1 ? launch_doc_tiles<NW, ND, 1>(c, A, lds)
            : tpt <= 2 ? launch_doc_tiles<NW, ND, 2>(c, A, lds)
                       : launch_doc_tiles<NW, ND, 4>(c, A, lds);
@@ -914,7 +916,7 @@ bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps)
 {
     if (mh_steps < 1 || mh_steps > 4) return false;
     if (c->opt.proposal_mode == 2 || (c->opt.proposal_mode == 1 && mh_steps != 1)) return false;
-    return tokens_per_thread(c) <= 4;
+    return (c->chunk_tokens + c->sweep_block - 1) / c->sweep_block <= 4;
 }
 
 // Work lists of the word pass from the word segment offsets.
@@ -1005,8 +1007,14 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
     A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias; A.cap = c->d_cap;
     A.zt = c->d_zt; A.zt_pack16 = c->zt_pack16 ? 1 : 0; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
     A.n_chunks = c->n_chunks; A.n_row_items = c->n_row_items; A.n_pieces = c->n_gather_pieces;
-    A.K = c->K; A.cap_tokens = c->chunk_tokens;
+    A.K = c->K; A.cap_tokens = c->chunk_tokens; A.max_doc_tokens = c->chunk_tokens;
+    A.doc_block = c->sweep_block;
     A.tile_lds_ints = (int32_t)(doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs) / sizeof(int32_t));
+    if (nw + nd <= 2 && c->n_chunks2 > 0) {  // short chains: the tiling with larger tiles
+        A.chunk_doc = c->d_chunk_doc2; A.tokdoc = c->d_tokdoc2; A.n_chunks = c->n_chunks2;
+        A.cap_tokens = c->chunk_tokens2; A.doc_block = c->sweep_block2;
+        A.tile_lds_ints = (int32_t)(doc_tile_lds_bytes(c->chunk_tokens2, c->chunk_docs2) / sizeof(int32_t));
+    }
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
     A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
     A.metaA = c->d_metaA; A.metaB = c->d_metaB; A.ma = c->d_ma; A.hs = c->d_hs;

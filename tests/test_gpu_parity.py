@@ -108,6 +108,22 @@ def test_long_documents_default_tiles(lda_mod, oracle_mod):
              docs=[0, 2, 5, 13, 16, len(doff) - 2])
 
 
+@pytest.mark.parametrize("mh", [1, 2, 3])
+def test_document_lengths_around_the_tile_sizes(lda_mod, oracle_mod, mh):
+    """Default tiles: chains of one and two steps run on larger tiles than longer chains, and
+    a document is long for both above the smaller tile size."""
+    V = 200
+    rng = np.random.default_rng(21)
+    lens = [1024, 3, 1025, 0, 1500, 511, 1536, 1537, 2, 3000, 1023, 1, 512, 513]
+    lens += list(rng.integers(0, 120, 60)) + [1024, 1024, 0]
+    doff = np.zeros(len(lens) + 1, np.int64)
+    doff[1:] = np.cumsum(lens)
+    p = 1.0 / np.arange(1, V + 1)
+    words = rng.choice(V, int(doff[-1]), p=p / p.sum()).astype(np.int32)
+    run_pair(lda_mod, oracle_mod, doff, words, V, 30, 0.2, 0.01, 9, 2, mh,
+             docs=[0, 2, 3, 4, 6, 7, 9, 10, len(lens) - 3, len(lens) - 1])
+
+
 def test_single_word_vocabulary(lda_mod, oracle_mod):
     doff = np.array([0, 3, 3, 10], np.int64)
     words = np.zeros(10, np.int32)
