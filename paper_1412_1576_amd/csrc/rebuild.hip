@@ -65,10 +65,19 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
     const int tid = threadIdx.x, nt = blockDim.x;
     for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
     __syncthreads();
-    for (int32_t p = t.p0 + tid; p < t.p1; p += nt) {
-        const uint32_t r = ((uint32_t)zw[(size_t)p << sh] & zmask) - (uint32_t)k0;
+    auto count = [&](int32_t rec) {
+        const uint32_t r = ((uint32_t)rec & zmask) - (uint32_t)k0;
         if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
+    };
+    int32_t p = t.p0 + tid;
+    for (; p + 3 * nt < t.p1; p += 4 * nt) {  // four loads in flight per thread
+        int32_t rec[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rec[u] = __builtin_nontemporal_load(&zw[(size_t)(p + u * nt) << sh]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) count(rec[u]);
     }
+    for (; p < t.p1; p += nt) count(zw[(size_t)p << sh]);
     __syncthreads();
     int32_t* __restrict__ row = nkw + (size_t)t.w * (size_t)K + (size_t)k0;
     if (t.multi == 1) {
@@ -131,23 +140,48 @@ __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* __restrict__ p, 
         p[i] = v;
 }
 
-// n_k: each block histograms a contiguous slice of z in LDS, then adds its
-// non-zero bins to the (pre-zeroed) global row.
-__global__ __launch_bounds__(1024) void nk_hist_kernel(const int32_t* __restrict__ z, int64_t N,
-                                                       int32_t K, int32_t* __restrict__ nk)
+constexpr int32_t kNkRangeTopics = 36864;  // 144 KB of LDS counters per workgroup
+
+// n_k: each block histograms a contiguous slice of z in LDS, then adds its non-zero bins to
+// the (pre-zeroed) global row.  For K beyond one LDS histogram blockIdx.y selects a range of
+// `span` topics and every range reads all of z.
+__global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __restrict__ z,
+                                                              int64_t N, int32_t K, int32_t span,
+                                                              int32_t* __restrict__ nk)
 {
     extern __shared__ int32_t hist[];
+    const int32_t k0 = (int32_t)blockIdx.y * span;
+    const int32_t k1 = (k0 + span < K) ? k0 + span : K;
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < K; k += nt) hist[k] = 0;
+    for (int32_t k = tid; k < k1 - k0; k += nt) hist[k] = 0;
     __syncthreads();
-    const int64_t per = (N + gridDim.x - 1) / gridDim.x;
+    // blocks own runs of whole int4s; two int4 loads per thread are in flight together (one
+    // dword per thread and iteration left the kernel bound by load latency)
+    const int64_t n4 = N / 4;
+    const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
     const int64_t b = (int64_t)blockIdx.x * per;
-    const int64_t e = (b + per < N) ? b + per : N;
-    for (int64_t i = b + tid; i < e; i += nt) atomicAdd(&hist[z[i]], 1);
+    const int64_t e = (b + per < n4) ? b + per : n4;
+    using v4i = int32_t __attribute__((ext_vector_type(4)));
+    const v4i* __restrict__ z4 = reinterpret_cast<const v4i*>(z);
+    auto count = [&](int32_t t) {
+        if (t >= k0 && t < k1) atomicAdd(&hist[t - k0], 1);
+    };
+    int64_t i = b + tid;
+    for (; i + nt < e; i += 2 * (int64_t)nt) {
+        const v4i a = __builtin_nontemporal_load(&z4[i]);
+        const v4i c = __builtin_nontemporal_load(&z4[i + nt]);
+        count(a.x); count(a.y); count(a.z); count(a.w);
+        count(c.x); count(c.y); count(c.z); count(c.w);
+    }
+    if (i < e) {
+        const v4i a = __builtin_nontemporal_load(&z4[i]);
+        count(a.x); count(a.y); count(a.z); count(a.w);
+    }
+    if (blockIdx.x == 0 && tid < (int)(N - 4 * n4)) count(z[4 * n4 + tid]);
     __syncthreads();
-    for (int32_t k = tid; k < K; k += nt) {
+    for (int32_t k = tid; k < k1 - k0; k += nt) {
         const int32_t v = hist[k];
-        if (v) atomicAdd(&nk[k], v);
+        if (v) atomicAdd(&nk[k0 + k], v);
     }
 }
 
@@ -191,6 +225,29 @@ int launch_dense_rows(lda_ctx* c)
     return LDA_OK;
 }
 
+
+// n_k by LDS histograms (K <= 8 * kNkRangeTopics)
+int launch_nk_hist(lda_ctx* c)
+{
+    const int32_t K = c->K;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3(64), dim3(256), 0, c->stream, c->d_nk, (int64_t)K, 0);
+    LDA_HIP(c, hipGetLastError());
+    const int32_t nr = (K + kNkRangeTopics - 1) / kNkRangeTopics;
+    const int32_t span = (K + nr - 1) / nr;
+    int64_t blocks = (c->N + 65535) / 65536;
+    const int64_t most = nr > 1 ? 512 : 2048;
+    if (blocks > most) blocks = most;
+    if (blocks < 1) blocks = 1;
+    const size_t lds = sizeof(int32_t) * (size_t)span;
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_ranges_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(nk_hist_ranges_kernel, dim3((unsigned)blocks, (unsigned)nr), dim3(1024), lds,
+                       c->stream, c->d_z, c->N, K, span, c->d_nk);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
+
 }  // namespace
 
 int launch_rebuild(lda_ctx* c)
@@ -200,68 +257,19 @@ int launch_rebuild(lda_ctx* c)
         return fail(c, LDA_ERR_UNSUPPORTED, "count rebuild supports K <= %d", max_rebuild_topics());
     int rc = launch_dense_rows(c);
     if (rc != LDA_OK) return rc;
-    const size_t lds = sizeof(int32_t) * (size_t)K;
-    if (lds > 48 * 1024)
-        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(64), dim3(256), 0, c->stream, c->d_nk, (int64_t)K, 0);
-    LDA_HIP(c, hipGetLastError());
-    int64_t blocks = (c->N + 65535) / 65536;
-    if (blocks > 2048) blocks = 2048;
-    if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(nk_hist_kernel, dim3((unsigned)blocks), dim3(1024), lds, c->stream, c->d_z,
-                       c->N, K, c->d_nk);
-    LDA_HIP(c, hipGetLastError());
-    return LDA_OK;
+    return launch_nk_hist(c);
 }
 
-int launch_dense_rows_hybrid(lda_ctx* c) { return launch_dense_rows(c); }
-
-}  // namespace lda
-
-// ======================================================================================
-// Hybrid store (LightLDA Sec. 5): dense rows for the head words, for every other word a
-// list of its non-zero (topic, count) pairs in ascending topic order plus an
-// open-addressing hash row (load <= 1/2) for random lookups.
-// ======================================================================================
-namespace lda {
-
-namespace {
-
-
-// n_k for K beyond one LDS histogram: blockIdx.y selects a range of `span` topics
-__global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __restrict__ z,
-                                                              int64_t N, int32_t K, int32_t span,
-                                                              int32_t* __restrict__ nk)
-{
-    extern __shared__ int32_t hist[];
-    const int32_t k0 = (int32_t)blockIdx.y * span;
-    const int32_t k1 = (k0 + span < K) ? k0 + span : K;
-    const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < k1 - k0; k += nt) hist[k] = 0;
-    __syncthreads();
-    const int64_t per = (N + gridDim.x - 1) / gridDim.x;
-    const int64_t b = (int64_t)blockIdx.x * per;
-    const int64_t e = (b + per < N) ? b + per : N;
-    for (int64_t i = b + tid; i < e; i += nt) {
-        const int32_t t = z[i];
-        if (t >= k0 && t < k1) atomicAdd(&hist[t - k0], 1);
-    }
-    __syncthreads();
-    for (int32_t k = tid; k < k1 - k0; k += nt) {
-        const int32_t v = hist[k];
-        if (v) atomicAdd(&nk[k0 + k], v);
-    }
-}
-
-}  // namespace
-
+// Hybrid store (LightLDA Sec. 5): dense rows for the head words as above; for every other word
+// a list of its non-zero (topic, count) pairs in ascending topic order plus an open-addressing
+// hash row (load <= 1/2) for random lookups, both made from one global sort of the tail
+// words' (word, topic) keys (layout.hip).
 int launch_rebuild_hybrid(lda_ctx* c)
 {
     const int32_t K = c->K;
     // ---- word-major copy of z and the dense head rows ----
     {
-        const int rc = launch_dense_rows_hybrid(c);
+        const int rc = launch_dense_rows(c);
         if (rc != LDA_OK) return rc;
     }
     // ---- sparse rows: lists, lengths and hash rows by one global sort (layout.hip) ----
@@ -270,30 +278,8 @@ int launch_rebuild_hybrid(lda_ctx* c)
         if (rc != LDA_OK) return rc;
     }
     // ---- n_k ----
-    if (K > 8 * 32768) return launch_nk_by_sort(c);
-    hipLaunchKernelGGL(fill_i32_kernel, dim3(64), dim3(256), 0, c->stream, c->d_nk, (int64_t)K, 0);
-    LDA_HIP(c, hipGetLastError());
-    int64_t blocks = (c->N + 65535) / 65536;
-    if (blocks > 2048) blocks = 2048;
-    if (blocks < 1) blocks = 1;
-    const int32_t span = 32768;
-    if (K <= span) {
-        const size_t lds = sizeof(int32_t) * (size_t)K;
-        if (lds > 48 * 1024)
-            LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(nk_hist_kernel, dim3((unsigned)blocks), dim3(1024), lds, c->stream,
-                           c->d_z, c->N, K, c->d_nk);
-    } else {
-        const size_t lds = sizeof(int32_t) * (size_t)span;
-        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_ranges_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        if (blocks > 512) blocks = 512;
-        hipLaunchKernelGGL(nk_hist_ranges_kernel, dim3((unsigned)blocks, (K + span - 1) / span),
-                           dim3(1024), lds, c->stream, c->d_z, c->N, K, span, c->d_nk);
-    }
-    LDA_HIP(c, hipGetLastError());
-    return LDA_OK;
+    if (K > 8 * kNkRangeTopics) return launch_nk_by_sort(c);
+    return launch_nk_hist(c);
 }
 
 }  // namespace lda
