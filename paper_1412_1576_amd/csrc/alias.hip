@@ -217,42 +217,69 @@ __global__ __launch_bounds__(1024) void alias_beta_kernel(const int32_t* nk, int
 }
 
 // Non-zero topics of a dense row, ascending, into the word's list (a mixture word
-// that keeps a dense row).  One workgroup per word.
-__global__ __launch_bounds__(256) void compact_rows_kernel(const int32_t* __restrict__ words,
-                                                           const int32_t* __restrict__ nkw,
-                                                           int32_t K,
-                                                           const uint32_t* __restrict__ sp_off,
-                                                           int32_t* __restrict__ sp_topic,
-                                                           int32_t* __restrict__ sp_count,
-                                                           int32_t* __restrict__ sp_nnz)
+// that keeps a dense row).  One workgroup per word; every wave owns a contiguous run of
+// topics, counts its non-zeros, and after one barrier places them (the second read of the
+// run comes from L2).  Four loads per lane are in flight.
+__global__ __launch_bounds__(1024) void compact_rows_kernel(const int32_t* __restrict__ words,
+                                                            const int32_t* __restrict__ nkw,
+                                                            int32_t K,
+                                                            const uint32_t* __restrict__ sp_off,
+                                                            int32_t* __restrict__ sp_topic,
+                                                            int32_t* __restrict__ sp_count,
+                                                            int32_t* __restrict__ sp_nnz)
 {
-    __shared__ uint32_t wcnt[4];
+    __shared__ uint32_t wcnt[16];
     const int32_t w = words[blockIdx.x];
     const int32_t* __restrict__ row = nkw + (size_t)w * (size_t)K;
     const size_t off = sp_off[w];
     const int lane = threadIdx.x & (kWave - 1), wv = threadIdx.x >> 6;
     const int nw = blockDim.x >> 6;
-    uint32_t base = 0;
-    for (int32_t k0 = 0; k0 < K; k0 += (int32_t)blockDim.x) {
-        const int32_t k = k0 + (int32_t)threadIdx.x;
-        const int32_t v = (k < K) ? row[k] : 0;
+    const int32_t chunk = (((K + nw - 1) / nw) + kWave - 1) & ~(kWave - 1);
+    const int32_t kb0 = (wv * chunk < K) ? wv * chunk : K;
+    const int32_t kb1 = (kb0 + chunk < K) ? kb0 + chunk : K;
+    uint32_t cnt = 0;
+    int32_t kb = kb0;
+    for (; kb + 4 * kWave <= kb1; kb += 4 * kWave) {
+        int32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = row[kb + u * kWave + lane];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) cnt += (uint32_t)__popcll(__ballot(v[u] > 0));
+    }
+    for (; kb < kb1; kb += kWave) {
+        const int32_t k = kb + lane;
+        const int32_t v = (k < kb1) ? row[k] : 0;
+        cnt += (uint32_t)__popcll(__ballot(v > 0));
+    }
+    if (lane == 0) wcnt[wv] = cnt;
+    __syncthreads();
+    uint32_t pos = 0, total = 0;
+    for (int i = 0; i < nw; ++i) {
+        if (i < wv) pos += wcnt[i];
+        total += wcnt[i];
+    }
+    auto place = [&](int32_t k, int32_t v) {
         const uint64_t mask = __ballot(v > 0);
-        __syncthreads();
-        if (lane == 0) wcnt[wv] = (uint32_t)__popcll(mask);
-        __syncthreads();
-        uint32_t before = 0, total = 0;
-        for (int i = 0; i < nw; ++i) {
-            if (i < wv) before += wcnt[i];
-            total += wcnt[i];
-        }
         if (v > 0) {
-            const size_t p = off + base + before + rank_below(mask);
+            const size_t p = off + pos + rank_below(mask);
             sp_topic[p] = k;
             sp_count[p] = v;
         }
-        base += total;
+        pos += (uint32_t)__popcll(mask);
+    };
+    kb = kb0;
+    for (; kb + 4 * kWave <= kb1; kb += 4 * kWave) {
+        int32_t v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = row[kb + u * kWave + lane];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) place(kb + u * kWave + lane, v[u]);
     }
-    if (threadIdx.x == 0) sp_nnz[w] = (int32_t)base;
+    for (; kb < kb1; kb += kWave) {
+        const int32_t k = kb + lane;
+        place(k, (k < kb1) ? row[k] : 0);
+    }
+    if (threadIdx.x == 0) sp_nnz[w] = (int32_t)total;
 }
 
 template <class Kern>
@@ -320,14 +347,26 @@ int launch_alias_build_hybrid(lda_ctx* c)
                                c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr,
                                use_cache, nullptr);
         } else {
-            hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, c->stream, c->d_nk,
-                               K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
-                               c->d_big_ws);
+            // one workgroup for milliseconds: on a stream of its own (default priority), forked
+            // from the caller's stream here and joined after the last table kernel
+            if (!c->side_stream) {
+                LDA_HIP(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
+                LDA_HIP(c, hipEventCreateWithFlags(&c->side_fork, hipEventDisableTiming));
+                LDA_HIP(c, hipEventCreateWithFlags(&c->side_join, hipEventDisableTiming));
+            }
+            LDA_HIP(c, hipEventRecord(c->side_fork, c->stream));
+            LDA_HIP(c, hipStreamWaitEvent(c->side_stream, c->side_fork, 0));
+            hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, c->side_stream,
+                               c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
+                               c->d_big_ws + c->big_ws_stride * (size_t)c->n_big_wg);
+            LDA_HIP(c, hipGetLastError());
+            LDA_HIP(c, hipEventRecord(c->side_join, c->side_stream));
+            c->side_pending = true;
         }
         LDA_HIP(c, hipGetLastError());
     }
     if (c->n_compact > 0) {
-        hipLaunchKernelGGL(compact_rows_kernel, dim3(c->n_compact), dim3(256), 0, c->stream,
+        hipLaunchKernelGGL(compact_rows_kernel, dim3(c->n_compact), dim3(K <= 4096 ? 256 : 1024), 0, c->stream,
                            c->d_compact_words, c->d_nkw, K, c->d_sp_off, c->d_sp_topic,
                            c->d_sp_count, c->d_sp_nnz);
         LDA_HIP(c, hipGetLastError());
@@ -353,6 +392,15 @@ int launch_alias_build_hybrid(lda_ctx* c)
         }
         LDA_HIP(c, hipGetLastError());
     }
+    return LDA_OK;
+}
+
+// The caller's stream waits for what launch_alias_build_hybrid put on the side stream.
+int join_side_stream(lda_ctx* c)
+{
+    if (!c->side_pending) return LDA_OK;
+    c->side_pending = false;
+    LDA_HIP(c, hipStreamWaitEvent(c->stream, c->side_join, 0));
     return LDA_OK;
 }
 

@@ -67,7 +67,14 @@ void free_all(lda_ctx* c)
     for (hipEvent_t& e : c->pass_ev) {
         if (e) (void)hipEventDestroy(e);
         e = nullptr;
-    } dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
+    }
+    if (c->side_stream) (void)hipStreamSynchronize(c->side_stream);
+    if (c->side_fork) (void)hipEventDestroy(c->side_fork);
+    if (c->side_join) (void)hipEventDestroy(c->side_join);
+    if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
+    c->side_fork = c->side_join = nullptr;
+    c->side_stream = nullptr;
+    dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
     dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_chunk_doc2); dev_free(c->d_tokdoc2); dev_free(c->d_long_doc);
     dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
     dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
@@ -196,9 +203,10 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
                           c->n_mix_class[kMixClasses - 1] > 0;
     if (need_big) {
         c->big_ws_stride = (alias_list_bytes_host((size_t)K) + 255) / 256 * 256;
-        int64_t wg = (int64_t)(2.0e9 / (double)c->big_ws_stride);
+        // one workgroup per compute unit when 12 GB allow it (K = 10^6: 256 x 40 MB)
+        int64_t wg = (int64_t)(12.0e9 / (double)c->big_ws_stride);
         c->n_big_wg = (int32_t)std::max<int64_t>(1, std::min<int64_t>(256, wg));
-        AL(d_big_ws, c->big_ws_stride * (size_t)c->n_big_wg, "table workspace");
+        AL(d_big_ws, c->big_ws_stride * ((size_t)c->n_big_wg + 1), "table workspace");
     }
 #undef AL
     return LDA_OK;
@@ -471,6 +479,8 @@ int lda_build_alias(lda_ctx* c)
             rc = launch_alias_mix_class(c, c->d_mix_class[cl], c->n_mix_class[cl],
                                         cap < 0 ? 0 : (cap ? cap : max_lds_table_entries()));
         }
+        const int rj = join_side_stream(c);
+        if (rc == LDA_OK) rc = rj;
     } else {
         rc = launch_alias_build(c);
     }

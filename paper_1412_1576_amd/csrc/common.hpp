@@ -142,7 +142,11 @@ struct lda_ctx {
     uint64_t* d_beta_hdr = nullptr;      // [2] QB, capacity
     unsigned char* d_big_ws = nullptr;   // list memory of the workgroups that build big tables
     size_t big_ws_stride = 0;
-    int32_t n_big_wg = 0;
+    int32_t n_big_wg = 0;                // the shared beta table has one more slot of its own
+    // the one-workgroup build of a large beta table runs beside the other table kernels
+    hipStream_t side_stream = nullptr;
+    hipEvent_t side_fork = nullptr, side_join = nullptr;
+    bool side_pending = false;           // side_join recorded, not yet waited for
     int64_t total_list = 0, total_hash = 0;
     std::vector<int32_t> h_wcount;       // corpus frequency of every word
     std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table
@@ -189,6 +193,7 @@ int launch_alias_build_hybrid(lda_ctx* c);
 int launch_rebuild_hybrid(lda_ctx* c);
 int launch_sweep_hybrid(lda_ctx* c, int32_t mh_steps);
 int launch_loglik_word_hybrid(lda_ctx* c, double* word_part);
+int join_side_stream(lda_ctx* c);
 int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries);
 int max_lds_table_entries();  // largest alias table built in LDS
 
