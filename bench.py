@@ -53,7 +53,7 @@ def doc_pass_bytes_per_token(mh_steps: int) -> float:
 # fetched + written); keyed by (workload, mh_steps, dense_alias_min_count).  None where not
 # measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2, 10000): (17_985_367.7 * 2.000 + 12_673_646.1 * 1.000) * 1024.0,
+    ("c3", 2, 10000): (17_920_249.3 * 2.000 + 12_494_336.2 * 1.000) * 1024.0,
 }
 
 
