@@ -349,19 +349,12 @@ int launch_alias_build_hybrid(lda_ctx* c)
         } else {
             // one workgroup for milliseconds: on a stream of its own (default priority), forked
             // from the caller's stream here and joined after the last table kernel
-            if (!c->side_stream) {
-                LDA_HIP(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
-                LDA_HIP(c, hipEventCreateWithFlags(&c->side_fork, hipEventDisableTiming));
-                LDA_HIP(c, hipEventCreateWithFlags(&c->side_join, hipEventDisableTiming));
-            }
-            LDA_HIP(c, hipEventRecord(c->side_fork, c->stream));
-            LDA_HIP(c, hipStreamWaitEvent(c->side_stream, c->side_fork, 0));
+            if ((rc = fork_side_stream(c)) != LDA_OK) return rc;
             hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, c->side_stream,
                                c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
                                c->d_big_ws + c->big_ws_stride * (size_t)c->n_big_wg);
             LDA_HIP(c, hipGetLastError());
-            LDA_HIP(c, hipEventRecord(c->side_join, c->side_stream));
-            c->side_pending = true;
+            if ((rc = side_stream_done(c)) != LDA_OK) return rc;
         }
         LDA_HIP(c, hipGetLastError());
     }
@@ -392,15 +385,6 @@ int launch_alias_build_hybrid(lda_ctx* c)
         }
         LDA_HIP(c, hipGetLastError());
     }
-    return LDA_OK;
-}
-
-// The caller's stream waits for what launch_alias_build_hybrid put on the side stream.
-int join_side_stream(lda_ctx* c)
-{
-    if (!c->side_pending) return LDA_OK;
-    c->side_pending = false;
-    LDA_HIP(c, hipStreamWaitEvent(c->stream, c->side_join, 0));
     return LDA_OK;
 }
 

@@ -87,6 +87,41 @@ void free_all(lda_ctx* c)
     dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
 }
 
+}  // namespace
+
+int fork_side_stream(lda_ctx* c)
+{
+    if (c->side_pending) {
+        const int rc = join_side_stream(c);
+        if (rc != LDA_OK) return rc;
+    }
+    if (!c->side_stream) {
+        LDA_HIP(c, hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking));
+        LDA_HIP(c, hipEventCreateWithFlags(&c->side_fork, hipEventDisableTiming));
+        LDA_HIP(c, hipEventCreateWithFlags(&c->side_join, hipEventDisableTiming));
+    }
+    LDA_HIP(c, hipEventRecord(c->side_fork, c->stream));
+    LDA_HIP(c, hipStreamWaitEvent(c->side_stream, c->side_fork, 0));
+    return LDA_OK;
+}
+
+int side_stream_done(lda_ctx* c)
+{
+    LDA_HIP(c, hipEventRecord(c->side_join, c->side_stream));
+    c->side_pending = true;
+    return LDA_OK;
+}
+
+int join_side_stream(lda_ctx* c)
+{
+    if (!c->side_pending) return LDA_OK;
+    c->side_pending = false;
+    LDA_HIP(c, hipStreamWaitEvent(c->stream, c->side_join, 0));
+    return LDA_OK;
+}
+
+namespace {
+
 template <class T>
 int upload(lda_ctx* c, T** dst, const std::vector<T>& v, const char* what)
 {

@@ -193,6 +193,12 @@ int launch_alias_build_hybrid(lda_ctx* c);
 int launch_rebuild_hybrid(lda_ctx* c);
 int launch_sweep_hybrid(lda_ctx* c, int32_t mh_steps);
 int launch_loglik_word_hybrid(lda_ctx* c, double* word_part);
+// A second stream of the library's own (default priority) for kernels that can run beside
+// the caller's stream: fork (the side stream waits for everything queued on the caller's
+// stream so far), launch on c->side_stream, side_stream_done, and later join (the caller's
+// stream waits for the side stream).  One fork may be pending at a time.
+int fork_side_stream(lda_ctx* c);
+int side_stream_done(lda_ctx* c);
 int join_side_stream(lda_ctx* c);
 int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries);
 int max_lds_table_entries();  // largest alias table built in LDS

@@ -1014,6 +1014,10 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
         A.chunk_doc = c->d_chunk_doc2; A.tokdoc = c->d_tokdoc2; A.n_chunks = c->n_chunks2;
         A.cap_tokens = c->chunk_tokens2; A.doc_block = c->sweep_block2;
         A.tile_lds_ints = (int32_t)(doc_tile_lds_bytes(c->chunk_tokens2, c->chunk_docs2) / sizeof(int32_t));
+    } else if (c->n_chunks2 > 0) {
+        // longer chains (default tiles): one token per thread keeps the chain's registers low
+        // enough for two 1024-thread workgroups per CU (4 steps: 28.9 instead of 33.4 ms)
+        A.doc_block = std::min(1024, (c->chunk_tokens + 63) / 64 * 64);
     }
     A.alpha = c->alpha; A.beta = c->beta; A.alphabar = c->alphabar; A.betabar = c->betabar;
     A.seed_lo = (uint32_t)c->seed; A.seed_hi = (uint32_t)(c->seed >> 32); A.sweep = c->sweep_index;
