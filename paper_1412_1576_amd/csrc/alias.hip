@@ -162,6 +162,7 @@ struct MixArgs {
     int32_t use_cache;
     unsigned char* ws;
     size_t ws_stride;
+    int32_t* next;  // big tables: work counter, zero at launch
 };
 
 template <bool GLOBAL>
@@ -190,12 +191,22 @@ __global__ __launch_bounds__(256) void alias_mix_lds_kernel(MixArgs a)
 
 __global__ __launch_bounds__(1024) void alias_mix_big_kernel(MixArgs a)
 {
+    // The tables differ in size by orders of magnitude and are listed largest first: a
+    // workgroup takes its first table by its index and every further one from a counter.
+    __shared__ int32_t s_next;
     unsigned char* lists = a.ws + (size_t)blockIdx.x * a.ws_stride;
-    for (int32_t i = blockIdx.x; i < a.n_words; i += gridDim.x) {
+    int32_t i = blockIdx.x;
+    while (i < a.n_words) {
         mix_table<true>(a, a.words[i], lists);
         ListMem<true>::barrier();
+        if (threadIdx.x == 0) s_next = (int32_t)gridDim.x + atomicAdd(a.next, 1);
+        __syncthreads();
+        i = s_next;
+        __syncthreads();
     }
 }
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
 
 template <bool GLOBAL>
 __global__ __launch_bounds__(1024) void alias_beta_kernel(const int32_t* nk, int32_t K, double beta,
@@ -328,69 +339,12 @@ int launch_alias_build(lda_ctx* c)
     return LDA_OK;
 }
 
-// hybrid mode: beta table, dense tables of the head words, mixture tables of the rest
-int launch_alias_build_hybrid(lda_ctx* c)
-{
-    const int32_t K = c->K;
-    const int lds_max = max_lds_table_entries();
-    int rc;
-    if (c->n_mix > 0) {
-        if (K <= lds_max) {
-            size_t lds;
-            int32_t use_cache;
-            lds_plan((size_t)K, lds, use_cache);
-            rc = set_lds(c, alias_beta_kernel<false>, lds);
-            if (rc != LDA_OK) return rc;
-            int nw = (K + kWave - 1) / kWave;
-            if (nw > kMaxWaves) nw = kMaxWaves;
-            hipLaunchKernelGGL(alias_beta_kernel<false>, dim3(1), dim3(nw * kWave), lds, c->stream,
-                               c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr,
-                               use_cache, nullptr);
-        } else {
-            // one workgroup for milliseconds: on a stream of its own (default priority), forked
-            // from the caller's stream here and joined after the last table kernel
-            if ((rc = fork_side_stream(c)) != LDA_OK) return rc;
-            hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, c->side_stream,
-                               c->d_nk, K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
-                               c->d_big_ws + c->big_ws_stride * (size_t)c->n_big_wg);
-            LDA_HIP(c, hipGetLastError());
-            if ((rc = side_stream_done(c)) != LDA_OK) return rc;
-        }
-        LDA_HIP(c, hipGetLastError());
-    }
-    if (c->n_compact > 0) {
-        hipLaunchKernelGGL(compact_rows_kernel, dim3(c->n_compact), dim3(K <= 4096 ? 256 : 1024), 0, c->stream,
-                           c->d_compact_words, c->d_nkw, K, c->d_sp_off, c->d_sp_topic,
-                           c->d_sp_count, c->d_sp_nnz);
-        LDA_HIP(c, hipGetLastError());
-    }
-    if (c->n_dense_alias > 0) {
-        DenseArgs a{};
-        a.words = c->d_dense_alias_words; a.n_words = c->n_dense_alias; a.nkw = c->d_nkw;
-        a.nk = c->d_nk; a.K = K; a.beta = c->beta; a.betabar = c->betabar; a.alias = c->d_alias;
-        a.cap = c->d_cap; a.metaA = c->d_metaA;
-        if (K <= lds_max) {
-            size_t lds;
-            lds_plan((size_t)K, lds, a.use_cache);
-            rc = set_lds(c, alias_dense_lds_kernel, lds);
-            if (rc != LDA_OK) return rc;
-            int nw = (K + kWave - 1) / kWave;
-            if (nw > kMaxWaves) nw = kMaxWaves;
-            hipLaunchKernelGGL(alias_dense_lds_kernel, dim3(c->n_dense_alias), dim3(nw * kWave), lds,
-                               c->stream, a);
-        } else {
-            a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
-            const int grid = c->n_dense_alias < c->n_big_wg ? c->n_dense_alias : c->n_big_wg;
-            hipLaunchKernelGGL(alias_dense_big_kernel, dim3(grid), dim3(1024), 0, c->stream, a);
-        }
-        LDA_HIP(c, hipGetLastError());
-    }
-    return LDA_OK;
-}
+namespace {
 
 // Mixture tables of the words in `words` whose list capacity is at most cap_entries
 // (cap_entries = 0: any size, built in the global workspace).
-int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries)
+int launch_alias_mix_class(lda_ctx* c, hipStream_t stream, const int32_t* words, int32_t n_words,
+                           int32_t cap_entries)
 {
     if (n_words <= 0) return LDA_OK;
     MixArgs a{};
@@ -404,14 +358,109 @@ int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, in
         if (rc != LDA_OK) return rc;
         int threads = ((cap_entries + kWave - 1) / kWave) * kWave;
         if (threads > 256) threads = 256;
-        hipLaunchKernelGGL(alias_mix_lds_kernel, dim3(n_words), dim3(threads), lds, c->stream, a);
+        hipLaunchKernelGGL(alias_mix_lds_kernel, dim3(n_words), dim3(threads), lds, stream, a);
     } else {
         a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
+        a.next = c->d_flag + 1;
+        hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, stream, a.next, 0);
+        LDA_HIP(c, hipGetLastError());
         const int grid = n_words < c->n_big_wg ? n_words : c->n_big_wg;
-        hipLaunchKernelGGL(alias_mix_big_kernel, dim3(grid), dim3(1024), 0, c->stream, a);
+        hipLaunchKernelGGL(alias_mix_big_kernel, dim3(grid), dim3(1024), 0, stream, a);
     }
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
+}
+
+// the shared beta table and the mixture tables that are built in LDS, in this order on `stream`
+int launch_small_mixture_tables(lda_ctx* c, hipStream_t stream)
+{
+    const int32_t K = c->K;
+    const int lds_max = max_lds_table_entries();
+    int rc;
+    if (K <= lds_max) {
+        size_t lds;
+        int32_t use_cache;
+        lds_plan((size_t)K, lds, use_cache);
+        rc = set_lds(c, alias_beta_kernel<false>, lds);
+        if (rc != LDA_OK) return rc;
+        int nw = (K + kWave - 1) / kWave;
+        if (nw > kMaxWaves) nw = kMaxWaves;
+        hipLaunchKernelGGL(alias_beta_kernel<false>, dim3(1), dim3(nw * kWave), lds, stream, c->d_nk,
+                           K, c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, use_cache, nullptr);
+    } else {  // one workgroup, with a slot of list memory of its own
+        hipLaunchKernelGGL(alias_beta_kernel<true>, dim3(1), dim3(1024), 0, stream, c->d_nk, K,
+                           c->beta, c->betabar, c->d_beta_alias, c->d_beta_hdr, 1,
+                           c->d_big_ws + c->big_ws_stride * (size_t)c->n_big_wg);
+    }
+    LDA_HIP(c, hipGetLastError());
+    for (int cl = 0; cl < kMixClasses; ++cl) {
+        const int32_t cap = kMixClassCap[cl];
+        if (cap < 0) continue;  // the class of the global workspace
+        rc = launch_alias_mix_class(c, stream, c->d_mix_class[cl], c->n_mix_class[cl],
+                                    cap ? cap : lds_max);
+        if (rc != LDA_OK) return rc;
+    }
+    return LDA_OK;
+}
+
+}  // namespace
+
+// Hybrid mode: the shared beta table, dense tables of the head words, mixture tables of the
+// rest.  Two chains of kernels run side by side: on a second stream of the library's own the
+// beta table (one workgroup, milliseconds when K is large) and the many small tables built in
+// LDS; on the caller's stream the dense tables and the tables built in the global workspace.
+// The second stream is forked from the caller's by an event and joined at the end.
+int launch_alias_build_hybrid(lda_ctx* c)
+{
+    const int32_t K = c->K;
+    const int lds_max = max_lds_table_entries();
+    int rc;
+    if (c->n_compact > 0) {  // lists the mixture tables below are built from
+        hipLaunchKernelGGL(compact_rows_kernel, dim3(c->n_compact), dim3(K <= 4096 ? 256 : 1024), 0,
+                           c->stream, c->d_compact_words, c->d_nkw, K, c->d_sp_off, c->d_sp_topic,
+                           c->d_sp_count, c->d_sp_nnz);
+        LDA_HIP(c, hipGetLastError());
+    }
+    if (c->n_mix > 0) {
+        if ((rc = fork_side_stream(c)) != LDA_OK) return rc;
+        rc = launch_small_mixture_tables(c, c->side_stream);
+        const int rd = side_stream_done(c);
+        if (rc != LDA_OK || rd != LDA_OK) {
+            (void)join_side_stream(c);
+            return rc != LDA_OK ? rc : rd;
+        }
+    }
+    if (c->n_dense_alias > 0) {
+        DenseArgs a{};
+        a.words = c->d_dense_alias_words; a.n_words = c->n_dense_alias; a.nkw = c->d_nkw;
+        a.nk = c->d_nk; a.K = K; a.beta = c->beta; a.betabar = c->betabar; a.alias = c->d_alias;
+        a.cap = c->d_cap; a.metaA = c->d_metaA;
+        if (K <= lds_max) {
+            size_t lds;
+            lds_plan((size_t)K, lds, a.use_cache);
+            rc = set_lds(c, alias_dense_lds_kernel, lds);
+            if (rc == LDA_OK) {
+                int nw = (K + kWave - 1) / kWave;
+                if (nw > kMaxWaves) nw = kMaxWaves;
+                hipLaunchKernelGGL(alias_dense_lds_kernel, dim3(c->n_dense_alias), dim3(nw * kWave),
+                                   lds, c->stream, a);
+            }
+        } else {
+            a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
+            const int grid = c->n_dense_alias < c->n_big_wg ? c->n_dense_alias : c->n_big_wg;
+            hipLaunchKernelGGL(alias_dense_big_kernel, dim3(grid), dim3(1024), 0, c->stream, a);
+            rc = LDA_OK;
+        }
+        if (rc == LDA_OK && hipGetLastError() != hipSuccess)
+            rc = fail(c, LDA_ERR_HIP, "launch of the dense table build failed");
+    } else {
+        rc = LDA_OK;
+    }
+    if (rc == LDA_OK)
+        rc = launch_alias_mix_class(c, c->stream, c->d_mix_class[kMixClasses - 1],
+                                    c->n_mix_class[kMixClasses - 1], 0);
+    const int rj = join_side_stream(c);
+    return rc != LDA_OK ? rc : rj;
 }
 
 }  // namespace lda

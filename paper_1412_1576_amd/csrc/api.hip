@@ -215,6 +215,12 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     UP(d_dense_alias_words, dense_alias, "dense-table words");
     UP(d_sparse_words, sparse, "sparse-row words");
     UP(d_compact_words, compact, "compaction words");
+    {  // the tables built in the global workspace: largest list first (see alias_mix_big_kernel)
+        std::vector<int32_t>& big = mixc[kMixClasses - 1];
+        std::stable_sort(big.begin(), big.end(), [&](int32_t a, int32_t b) {
+            return c->h_sp_off[a + 1] - c->h_sp_off[a] > c->h_sp_off[b + 1] - c->h_sp_off[b];
+        });
+    }
     for (int i = 0; i < kMixClasses; ++i) {
         c->n_mix_class[i] = (int32_t)mixc[i].size();
         UP(d_mix_class[i], mixc[i], "mixture class");
@@ -509,13 +515,6 @@ int lda_build_alias(lda_ctx* c)
     int rc;
     if (c->hybrid) {
         rc = launch_alias_build_hybrid(c);
-        for (int cl = 0; cl < kMixClasses && rc == LDA_OK; ++cl) {
-            const int32_t cap = kMixClassCap[cl];  // launch_alias_mix_class: 0 = global workspace
-            rc = launch_alias_mix_class(c, c->d_mix_class[cl], c->n_mix_class[cl],
-                                        cap < 0 ? 0 : (cap ? cap : max_lds_table_entries()));
-        }
-        const int rj = join_side_stream(c);
-        if (rc == LDA_OK) rc = rj;
     } else {
         rc = launch_alias_build(c);
     }

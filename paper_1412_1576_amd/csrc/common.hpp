@@ -200,7 +200,6 @@ int launch_loglik_word_hybrid(lda_ctx* c, double* word_part);
 int fork_side_stream(lda_ctx* c);
 int side_stream_done(lda_ctx* c);
 int join_side_stream(lda_ctx* c);
-int launch_alias_mix_class(lda_ctx* c, const int32_t* words, int32_t n_words, int32_t cap_entries);
 int max_lds_table_entries();  // largest alias table built in LDS
 
 // Up to this many topics the doc pass keeps a copy of n_k in every workgroup's LDS.
