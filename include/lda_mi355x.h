@@ -76,8 +76,8 @@ typedef struct lda_options {
 /*
  * lda_init -- take a corpus and set up the sampler state (problem statement: Sec. 3).
  *   D            number of documents (>= 1); empty documents are legal
- *   V, K         vocabulary size and number of topics (>= 1); K <= 2^20 - 2, and K <= 12288
- *                unless the hybrid store is selected (LDA_ERR_UNSUPPORTED otherwise)
+ *   V, K         vocabulary size and number of topics (>= 1); K <= 2^20 - 2; dense rows and
+ *                dense tables are limited to 10^10 and 4 * 10^9 entries (LDA_ERR_UNSUPPORTED)
  *   doc_offsets  [D+1] host, doc_offsets[0] = 0, non-decreasing, N = doc_offsets[D] in [1, 2^31-2]
  *   word_ids     [N] host, each in [0, V)
  *   alpha, beta  symmetric Dirichlet parameters (> 0) of Eq. (1)

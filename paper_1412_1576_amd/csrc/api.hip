@@ -321,15 +321,13 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
     for (int i = 0; i < 8; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
-    const bool hybrid = (o.dense_rows != 0) || (o.dense_alias_min_count != 0);
+    // The kernels of the all-dense case keep a whole row or table in LDS; beyond their K the
+    // general ones (topic ranges, tables in a global workspace) take over, with every row dense.
+    const bool hybrid = (o.dense_rows != 0) || (o.dense_alias_min_count != 0) ||
+                        K > max_alias_topics() || K > max_rebuild_topics();
     const int32_t H = o.dense_rows < 0 ? 0 : (o.dense_rows == 0 ? V : std::min(o.dense_rows, V));
     if (K > kMaxPackedTopics)
         return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: K must be < 2^20 - 1");
-    if (!hybrid && (K > max_alias_topics() || K > max_rebuild_topics()))
-        return fail(nullptr, LDA_ERR_UNSUPPORTED,
-                    "lda_init: K = %d exceeds the all-dense limit %d; use the hybrid store "
-                    "(dense_rows, dense_alias_min_count)", K,
-                    std::min(max_alias_topics(), max_rebuild_topics()));
     if ((double)H * (double)K > 1.0e10)
         return fail(nullptr, LDA_ERR_UNSUPPORTED, "lda_init: %d dense rows of %d topics are too large",
                     H, K);

@@ -140,7 +140,7 @@ def test_option_validation(lda_mod):
         lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, dense_rows=10,
                     dense_alias_min_count=1)
     assert e.value.code == lda_mod.LDA_ERR_ARG
-    # K beyond the all-dense limit points to the hybrid store
+    # more dense row entries than the library allocates
     with pytest.raises(lda_mod.LdaError) as e:
-        lda_mod.Lda(doff, words, cfg.V, 20000, cfg.alpha, cfg.beta)
+        lda_mod.Lda(doff, words, 20000, 600000, cfg.alpha, cfg.beta)
     assert e.value.code == lda_mod.LDA_ERR_UNSUPPORTED

@@ -5,6 +5,7 @@ the log-likelihood must agree to 1e-9 relative.
 """
 import numpy as np
 import pytest
+from scipy.special import gammaln
 
 from paper_1412_1576_amd import corpus
 
@@ -36,10 +37,13 @@ def check_state(g, o, docs=(), words=None, alias_words=None, tag=""):
     tg, dg, wg = g.loglik()
     to, do, wo = o.loglik()
     # the total to 1e-9 relative; a part may cancel to exactly 0 (K = 1), so the parts
-    # are held to the same absolute error as the total
-    assert abs(tg - to) <= LOGLIK_RTOL * abs(to), (tag, tg, to)
-    assert abs(dg - do) <= LOGLIK_RTOL * max(abs(do), abs(to)), (tag, dg, do)
-    assert abs(wg - wo) <= LOGLIK_RTOL * max(abs(wo), abs(to)), (tag, wg, wo)
+    # are held to the same absolute error as the total.  With K = 1 and V = 1 the total
+    # itself cancels to exactly 0: no sum of terms of size lgamma(N) can be closer to it
+    # than some ulps of that size, which is the floor of every bound (about 2e-7 at N = 10^5)
+    floor = 1024 * np.finfo(np.float64).eps * float(gammaln(g.N + 2.0))
+    assert abs(tg - to) <= max(LOGLIK_RTOL * abs(to), floor), (tag, tg, to)
+    assert abs(dg - do) <= max(LOGLIK_RTOL * max(abs(do), abs(to)), floor), (tag, dg, do)
+    assert abs(wg - wo) <= max(LOGLIK_RTOL * max(abs(wo), abs(to)), floor), (tag, wg, wo)
 
 
 def check_alias(g, o, words, tag=""):
