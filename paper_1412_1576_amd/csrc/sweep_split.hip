@@ -614,9 +614,12 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
     }
 }
 
-// Chains of up to two steps with up to two tokens per thread in 256-thread blocks (the
-// default tiling) are compiled for 7 waves per SIMD: one more resident workgroup per CU hides more of the gather latency
-// than the few registers it costs.
+// One workgroup per document tile; a thread runs the chains of up to T of its tokens,
+// interleaved.  Chains of up to two steps with up to two tokens per thread are compiled for
+// a fixed number of waves per SIMD (7 in blocks of up to 256 threads, 6 up to 768): one more
+// resident workgroup per CU hides more of the gather latency than the few registers it
+// costs.  Longer chains take the registers they need: two interleaved four-step chains use
+// about 100, one uses 62, which is why the launcher gives them one token per thread.
 //
 // NKL: the workgroup keeps a copy of n_k in LDS behind the tile (K <= kNkLdsTopics).  The
 // three n_k reads of a token are otherwise three separate requests to L2 (the array is larger
