@@ -57,6 +57,16 @@ typedef struct lda_ctx lda_ctx; /* opaque; owns all device memory of one corpus 
 /* Options for lda_init.  A zeroed struct (or a NULL pointer) selects the defaults. */
 typedef struct lda_options {
     void* hip_stream;              /* hipStream_t all work is enqueued on; NULL: the null stream */
+    /* Device allocator of the caller (e.g. a framework's caching allocator); both NULL: hipMalloc
+       and hipFree.  When set, every device buffer of the context -- at lda_init and the ones
+       that later calls grow or create on first use -- comes from dev_alloc(bytes, alloc_user),
+       which returns device memory aligned to 256 bytes or NULL (reported as LDA_ERR_OOM), and
+       goes back through dev_free(ptr, alloc_user), at lda_destroy at the latest.  The
+       callbacks run on the thread that calls the library; setting only one is LDA_ERR_ARG.
+       rocprim's temporary storage is requested through them as well. */
+    void* (*dev_alloc)(size_t bytes, void* alloc_user);
+    void (*dev_free)(void* ptr, void* alloc_user);
+    void* alloc_user;
     int32_t dense_rows;            /* hybrid store (Sec. 5): word ids [0, dense_rows) keep a dense n_kw
                                       row, the others a sorted (topic, count) list plus a hash row;
                                       0: every row dense; -1: no dense row */

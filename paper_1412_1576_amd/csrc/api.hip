@@ -23,6 +23,34 @@ int fail(lda_ctx* c, int code, const char* fmt, ...)
     return code;
 }
 
+int device_malloc(lda_ctx* c, void** p, size_t bytes, const char* what)
+{
+    *p = nullptr;
+    if (bytes == 0) bytes = 1;
+    if (c->opt.dev_alloc) {
+        *p = c->opt.dev_alloc(bytes, c->opt.alloc_user);
+        if (!*p)
+            return fail(c, LDA_ERR_OOM, "the caller's allocator returned NULL for %zu bytes (%s)",
+                        bytes, what);
+        return LDA_OK;
+    }
+    const hipError_t e = hipMalloc(p, bytes);
+    if (e != hipSuccess) {
+        *p = nullptr;
+        (void)hipGetLastError();
+        return fail(c, LDA_ERR_OOM, "device allocation of %zu bytes for %s failed: %s", bytes, what,
+                    hipGetErrorString(e));
+    }
+    return LDA_OK;
+}
+
+void device_free(lda_ctx* c, void* p)
+{
+    if (!p) return;
+    if (c->opt.dev_free) c->opt.dev_free(p, c->opt.alloc_user);
+    else (void)hipFree(p);
+}
+
 namespace {
 
 // bytes of list memory of the alias builder for n entries with the mass cache
@@ -33,37 +61,25 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff);
 template <class T>
 int dev_alloc(lda_ctx* c, T** p, size_t count, const char* what)
 {
-    *p = nullptr;
-    const size_t bytes = sizeof(T) * (count ? count : 1);
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
-    if (e != hipSuccess) {
-        *p = nullptr;
-        (void)hipGetLastError();
-        return fail(c, LDA_ERR_OOM, "device allocation of %zu bytes for %s failed: %s", bytes, what,
-                    hipGetErrorString(e));
-    }
-    return LDA_OK;
+    return device_malloc(c, p, count, what);
 }
 
 template <class T>
-void dev_free(T*& p)
+void dev_free(lda_ctx* c, T*& p)
 {
-    if (p) (void)hipFree(p);
+    device_free(c, p);
     p = nullptr;
 }
 
 void free_all(lda_ctx* c)
 {
-    dev_free(c->d_word); dev_free(c->d_doff); dev_free(c->d_z); dev_free(c->d_znew);
-    dev_free(c->d_gid); dev_free(c->d_wpos); dev_free(c->d_zt); dev_free(c->d_rec);
-    dev_free(c->d_row_items); dev_free(c->d_mix_items); dev_free(c->d_gather_pieces);
-    dev_free(c->d_sort_keys);
-    dev_free(c->d_sp_wloc); dev_free(c->d_sp_keys); dev_free(c->d_sp_sorted); dev_free(c->d_sp_runlen);
-    dev_free(c->d_sp_first); dev_free(c->d_sp_nruns);
-    if (c->d_sp_tmp) (void)hipFree(c->d_sp_tmp);
-    c->d_sp_tmp = nullptr;
-    if (c->d_sort_tmp) (void)hipFree(c->d_sort_tmp);
-    c->d_sort_tmp = nullptr;
+    dev_free(c, c->d_word); dev_free(c, c->d_doff); dev_free(c, c->d_z); dev_free(c, c->d_znew);
+    dev_free(c, c->d_gid); dev_free(c, c->d_wpos); dev_free(c, c->d_zt); dev_free(c, c->d_rec);
+    dev_free(c, c->d_row_items); dev_free(c, c->d_mix_items); dev_free(c, c->d_gather_pieces);
+    dev_free(c, c->d_sort_keys);
+    dev_free(c, c->d_sp_wloc); dev_free(c, c->d_sp_keys); dev_free(c, c->d_sp_sorted); dev_free(c, c->d_sp_runlen);
+    dev_free(c, c->d_sp_first); dev_free(c, c->d_sp_nruns);
+    dev_free(c, c->d_sp_tmp); dev_free(c, c->d_sort_tmp);
     for (hipEvent_t& e : c->pass_ev) {
         if (e) (void)hipEventDestroy(e);
         e = nullptr;
@@ -74,17 +90,17 @@ void free_all(lda_ctx* c)
     if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
     c->side_fork = c->side_join = nullptr;
     c->side_stream = nullptr;
-    dev_free(c->d_woff); dev_free(c->d_nkw); dev_free(c->d_nk);
-    dev_free(c->d_alias); dev_free(c->d_cap); dev_free(c->d_chunk_doc); dev_free(c->d_tokdoc); dev_free(c->d_chunk_doc2); dev_free(c->d_tokdoc2); dev_free(c->d_long_doc);
-    dev_free(c->d_long_slot); dev_free(c->d_long_keys); dev_free(c->d_long_cnts);
-    dev_free(c->d_tiles); dev_free(c->d_multi_words); dev_free(c->d_partial); dev_free(c->d_row);
-    dev_free(c->d_flag);
-    dev_free(c->d_dense_alias_words);
-    for (int i = 0; i < kMixClasses; ++i) dev_free(c->d_mix_class[i]);
-    dev_free(c->d_sparse_words); dev_free(c->d_compact_words); dev_free(c->d_sp_off);
-    dev_free(c->d_sp_topic); dev_free(c->d_sp_count); dev_free(c->d_sp_nnz); dev_free(c->d_hs_off);
-    dev_free(c->d_hs); dev_free(c->d_ma); dev_free(c->d_metaA); c->d_metaB = nullptr;
-    dev_free(c->d_beta_alias); dev_free(c->d_beta_hdr); dev_free(c->d_big_ws);
+    dev_free(c, c->d_woff); dev_free(c, c->d_nkw); dev_free(c, c->d_nk);
+    dev_free(c, c->d_alias); dev_free(c, c->d_cap); dev_free(c, c->d_chunk_doc); dev_free(c, c->d_tokdoc); dev_free(c, c->d_chunk_doc2); dev_free(c, c->d_tokdoc2); dev_free(c, c->d_long_doc);
+    dev_free(c, c->d_long_slot); dev_free(c, c->d_long_keys); dev_free(c, c->d_long_cnts);
+    dev_free(c, c->d_tiles); dev_free(c, c->d_multi_words); dev_free(c, c->d_partial); dev_free(c, c->d_row);
+    dev_free(c, c->d_flag);
+    dev_free(c, c->d_dense_alias_words);
+    for (int i = 0; i < kMixClasses; ++i) dev_free(c, c->d_mix_class[i]);
+    dev_free(c, c->d_sparse_words); dev_free(c, c->d_compact_words); dev_free(c, c->d_sp_off);
+    dev_free(c, c->d_sp_topic); dev_free(c, c->d_sp_count); dev_free(c, c->d_sp_nnz); dev_free(c, c->d_hs_off);
+    dev_free(c, c->d_hs); dev_free(c, c->d_ma); dev_free(c, c->d_metaA); c->d_metaB = nullptr;
+    dev_free(c, c->d_beta_alias); dev_free(c, c->d_beta_hdr); dev_free(c, c->d_big_ws);
 }
 
 }  // namespace
@@ -321,6 +337,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
     for (int i = 0; i < 8; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
+    if ((o.dev_alloc == nullptr) != (o.dev_free == nullptr))
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: dev_alloc and dev_free must be set together");
     // The kernels of the all-dense case keep a whole row or table in LDS; beyond their K the
     // general ones (topic ranges, tables in a global workspace) take over, with every row dense.
     const bool hybrid = (o.dense_rows != 0) || (o.dense_alias_min_count != 0) ||

@@ -178,6 +178,23 @@ namespace lda {
 
 int fail(lda_ctx* c, int code, const char* fmt, ...);
 
+// Device memory of a context: the caller's allocator (lda_options) or hipMalloc / hipFree.
+// device_malloc returns LDA_OK or records LDA_ERR_OOM; *p is NULL on failure.
+int device_malloc(lda_ctx* c, void** p, size_t bytes, const char* what);
+void device_free(lda_ctx* c, void* p);
+
+template <class T>
+int device_malloc(lda_ctx* c, T** p, size_t count, const char* what)
+{
+    return device_malloc(c, reinterpret_cast<void**>(p), sizeof(T) * (count ? count : 1), what);
+}
+
+#define LDA_ALLOC(ctx, ptr, count, what)                                                  \
+    do {                                                                                  \
+        const int rc__ = lda::device_malloc((ctx), (ptr), (size_t)(count), (what));       \
+        if (rc__ != LDA_OK) return rc__;                                                  \
+    } while (0)
+
 #define LDA_HIP(ctx, call)                                                              \
     do {                                                                                \
         hipError_t e__ = (call);                                                        \

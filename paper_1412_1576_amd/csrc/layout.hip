@@ -230,8 +230,8 @@ int launch_nk_by_sort(lda_ctx* c)
         size_t bytes = 0;
         LDA_HIP(c, rocprim::radix_sort_keys(nullptr, bytes, c->d_z, c->d_z, (size_t)N, 0u,
                                             (unsigned)end_bit, c->stream));
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sort_keys), sizeof(int32_t) * (size_t)N));
-        LDA_HIP(c, hipMalloc(&c->d_sort_tmp, bytes ? bytes : 1));
+        LDA_ALLOC(c, &c->d_sort_keys, N, "sorted topics");
+        LDA_ALLOC(c, reinterpret_cast<unsigned char**>(&c->d_sort_tmp), bytes, "sort workspace");
         c->sort_tmp_bytes = bytes;
     }
     size_t bytes = c->sort_tmp_bytes;
@@ -254,21 +254,21 @@ int launch_sparse_lists_by_sort(lda_ctx* c)
     while (tb < 31 && (1LL << tb) < (long long)c->K) ++tb;
     while (wb < 31 && (1LL << wb) < (long long)n_words) ++wb;
     if (!c->d_sp_first) {
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_first), sizeof(int32_t) * ((size_t)n_words + 2)));
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_nruns), sizeof(int32_t) * 2));
+        LDA_ALLOC(c, &c->d_sp_first, (size_t)n_words + 2, "first runs");
+        LDA_ALLOC(c, &c->d_sp_nruns, 2, "run count");
         LDA_HIP(c, hipMemsetAsync(c->d_sp_nruns, 0, sizeof(int32_t) * 2, c->stream));
         const size_t m = (size_t)(n > 0 ? n : 1);
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_wloc), sizeof(uint32_t) * m));
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_keys), sizeof(uint64_t) * m));
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_sorted), sizeof(uint64_t) * m));
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_sp_runlen), sizeof(uint32_t) * m));
+        LDA_ALLOC(c, &c->d_sp_wloc, m, "tail word indices");
+        LDA_ALLOC(c, &c->d_sp_keys, m, "(word, topic) keys");
+        LDA_ALLOC(c, &c->d_sp_sorted, m, "sorted keys");
+        LDA_ALLOC(c, &c->d_sp_runlen, m, "run lengths");
         size_t b1 = 0, b2 = 0;
         LDA_HIP(c, rocprim::radix_sort_keys(nullptr, b1, c->d_sp_keys, c->d_sp_sorted, (size_t)n, 0u,
                                             (unsigned)(tb + wb), c->stream));
         LDA_HIP(c, rocprim::run_length_encode(nullptr, b2, c->d_sp_sorted, (size_t)n, c->d_sp_keys,
                                               c->d_sp_runlen, c->d_sp_nruns, c->stream));
         c->sp_tmp_bytes = b1 > b2 ? b1 : b2;
-        LDA_HIP(c, hipMalloc(&c->d_sp_tmp, c->sp_tmp_bytes ? c->sp_tmp_bytes : 1));
+        LDA_ALLOC(c, reinterpret_cast<unsigned char**>(&c->d_sp_tmp), c->sp_tmp_bytes, "sort workspace");
         if (n > 0) {
             hipLaunchKernelGGL(sparse_wloc_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream,
                                c->d_woff, H, V, p0, n, c->d_sp_wloc);
@@ -312,20 +312,28 @@ int launch_layout(lda_ctx* c, const int32_t* /*h_word*/)
     const int64_t N = c->N;
     // stable radix sort of (word, CSR position) pairs: positions of one word stay ascending
     int32_t *keys_out = nullptr, *vals_in = nullptr;
-    LDA_HIP(c, hipMalloc(&keys_out, sizeof(int32_t) * N));
-    if (hipMalloc(&vals_in, sizeof(int32_t) * N) != hipSuccess) {
-        (void)hipFree(keys_out);
-        return fail(c, LDA_ERR_OOM, "layout: device allocation of %lld bytes failed",
-                    (long long)(sizeof(int32_t) * N));
+    void* tmp = nullptr;
+    auto release = [&]() {
+        device_free(c, tmp);
+        device_free(c, keys_out);
+        device_free(c, vals_in);
+    };
+    int rc = device_malloc(c, &keys_out, (size_t)N, "layout sort");
+    if (rc == LDA_OK) rc = device_malloc(c, &vals_in, (size_t)N, "layout sort");
+    if (rc != LDA_OK) {
+        release();
+        return rc;
     }
     hipLaunchKernelGGL(iota_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, vals_in, N);
     int end_bit = 1;
     while (end_bit < 31 && (1LL << end_bit) < (long long)c->V) ++end_bit;
     size_t tmp_bytes = 0;
-    void* tmp = nullptr;
     hipError_t e = rocprim::radix_sort_pairs(nullptr, tmp_bytes, c->d_word, keys_out, vals_in,
                                              c->d_gid, (size_t)N, 0u, (unsigned)end_bit, c->stream);
-    if (e == hipSuccess) e = hipMalloc(&tmp, tmp_bytes > 0 ? tmp_bytes : 1);
+    if (e == hipSuccess && (rc = device_malloc(c, &tmp, tmp_bytes, "layout sort")) != LDA_OK) {
+        release();
+        return rc;
+    }
     if (e == hipSuccess)
         e = rocprim::radix_sort_pairs(tmp, tmp_bytes, c->d_word, keys_out, vals_in, c->d_gid,
                                       (size_t)N, 0u, (unsigned)end_bit, c->stream);
@@ -335,12 +343,9 @@ int launch_layout(lda_ctx* c, const int32_t* /*h_word*/)
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    (void)hipFree(tmp);
-    (void)hipFree(keys_out);
-    (void)hipFree(vals_in);
+    release();
     if (e != hipSuccess)
-        return fail(c, e == hipErrorOutOfMemory ? LDA_ERR_OOM : LDA_ERR_HIP, "layout sort: %s",
-                    hipGetErrorString(e));
+        return fail(c, LDA_ERR_HIP, "layout sort: %s", hipGetErrorString(e));
 
     hipLaunchKernelGGL(invert_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_gid, N,
                        c->d_wpos);

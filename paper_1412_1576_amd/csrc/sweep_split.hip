@@ -897,16 +897,11 @@ template <class T>
 int grow(lda_ctx* c, T** p, size_t* have, size_t need, const char* what)
 {
     if (*have >= need) return LDA_OK;
-    if (*p) (void)hipFree(*p);
+    device_free(c, *p);
     *p = nullptr;
     *have = 0;
-    const hipError_t e = hipMalloc(reinterpret_cast<void**>(p), sizeof(T) * need);
-    if (e != hipSuccess) {
-        *p = nullptr;
-        (void)hipGetLastError();
-        return fail(c, LDA_ERR_OOM, "device allocation of %zu bytes for %s failed: %s",
-                    sizeof(T) * need, what, hipGetErrorString(e));
-    }
+    const int rc = device_malloc(c, p, need, what);
+    if (rc != LDA_OK) return rc;
     *have = need;
     return LDA_OK;
 }
@@ -967,19 +962,18 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
     c->n_row_items = (int32_t)items.size();
     c->n_mix_items = (int32_t)mix_items.size();
     if (!mix_items.empty()) {
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_mix_items), sizeof(int4) * mix_items.size()));
+        LDA_ALLOC(c, &c->d_mix_items, mix_items.size(), "word-pass work list");
         LDA_HIP(c, hipMemcpy(c->d_mix_items, mix_items.data(), sizeof(int4) * mix_items.size(),
                              hipMemcpyHostToDevice));
     }
     c->n_gather_pieces = (int32_t)pieces.size();
     if (!items.empty()) {
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_row_items), sizeof(int4) * items.size()));
+        LDA_ALLOC(c, &c->d_row_items, items.size(), "word-pass work list");
         LDA_HIP(c, hipMemcpy(c->d_row_items, items.data(), sizeof(int4) * items.size(),
                              hipMemcpyHostToDevice));
     }
     if (!pieces.empty()) {
-        LDA_HIP(c, hipMalloc(reinterpret_cast<void**>(&c->d_gather_pieces),
-                             sizeof(int4) * pieces.size()));
+        LDA_ALLOC(c, &c->d_gather_pieces, pieces.size(), "word-pass work list");
         LDA_HIP(c, hipMemcpy(c->d_gather_pieces, pieces.data(), sizeof(int4) * pieces.size(),
                              hipMemcpyHostToDevice));
     }

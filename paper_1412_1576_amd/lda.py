@@ -30,9 +30,16 @@ EXPORTS = [
 ]
 
 
+DEV_ALLOC = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+DEV_FREE = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+
+
 class lda_options(C.Structure):
     _fields_ = [
         ("hip_stream", C.c_void_p),
+        ("dev_alloc", DEV_ALLOC),
+        ("dev_free", DEV_FREE),
+        ("alloc_user", C.c_void_p),
         ("dense_rows", C.c_int32),
         ("dense_alias_min_count", C.c_int32),
         ("proposal_mode", C.c_int32),
@@ -110,7 +117,10 @@ class Lda:
 
     def __init__(self, doc_offsets, word_ids, V, K, alpha, beta, seed=0, stream=None,
                  dense_rows=0, dense_alias_min_count=0, proposal_mode=0, sweep_chunk_tokens=0,
-                 sweep_block_threads=0, rebuild_tile_tokens=0, time_sweep_passes=0):
+                 sweep_block_threads=0, rebuild_tile_tokens=0, time_sweep_passes=0,
+                 dev_alloc=None, dev_free=None):
+        """dev_alloc(bytes) -> device address (0: failure) and dev_free(address): the
+        caller's device allocator for every buffer of the context (both or neither)."""
         L = load_library()
         self._h = C.c_void_p()
         doc_offsets = np.ascontiguousarray(doc_offsets, np.int64)
@@ -124,6 +134,14 @@ class Lda:
         opt.sweep_block_threads = sweep_block_threads
         opt.rebuild_tile_tokens = rebuild_tile_tokens
         opt.time_sweep_passes = time_sweep_passes
+        # the ctypes thunks must outlive the context: the library calls them until lda_destroy
+        self._alloc_cb = self._free_cb = None
+        if dev_alloc is not None:
+            self._alloc_cb = DEV_ALLOC(lambda nbytes, user: int(dev_alloc(int(nbytes))) or None)
+            opt.dev_alloc = self._alloc_cb
+        if dev_free is not None:
+            self._free_cb = DEV_FREE(lambda ptr, user: dev_free(int(ptr or 0)))
+            opt.dev_free = self._free_cb
         self.D = len(doc_offsets) - 1
         self.V, self.K = int(V), int(K)
         rc = L.lda_init(C.byref(self._h), self.D, self.V, self.K, doc_offsets, word_ids,

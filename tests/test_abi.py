@@ -37,9 +37,10 @@ def test_exports_every_declared_symbol(lib):
 
 def test_options_struct_layout():
     from paper_1412_1576_amd import lda
-    # void* + 6 int32 + 9 reserved int32
-    assert C.sizeof(lda.lda_options) == 8 + 15 * 4 + 4  # padded to 8-byte alignment
-    assert lda.lda_options.dense_rows.offset == 8
+    # stream, the three allocator fields, 7 int32, 8 reserved int32
+    assert C.sizeof(lda.lda_options) == 4 * 8 + 15 * 4 + 4  # padded to 8-byte alignment
+    assert lda.lda_options.dev_alloc.offset == 8
+    assert lda.lda_options.dense_rows.offset == 32
 
 
 def test_bad_arguments_are_rejected_on_the_host(lib):
@@ -65,6 +66,8 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert init(doff=np.array([0, 3, 2], np.int64))[0] == lda.LDA_ERR_ARG
     assert init(doff=np.array([0, 0, 0], np.int64))[0] == lda.LDA_ERR_ARG  # empty corpus
     assert init(proposal_mode=3)[0] == lda.LDA_ERR_ARG
+    only_alloc = lda.DEV_ALLOC(lambda nbytes, user: None)
+    assert init(dev_alloc=only_alloc)[0] == lda.LDA_ERR_ARG  # dev_free missing
     rc, msg = init(K=0)
     assert "K" in msg
     # calls on a NULL context

@@ -222,6 +222,63 @@ def test_state_machine_and_checkpoint(lda_mod, oracle_mod):
     g.close(); h.close()
 
 
+@pytest.mark.parametrize("hybrid", [False, True])
+def test_caller_allocator(lda_mod, oracle_mod, hybrid):
+    """Every device buffer comes from the caller's allocator (here PyTorch's caching
+    allocator) and goes back to it; results are those of the default allocator."""
+    import torch
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=300)
+    doff, words = corpus.make_corpus(cfg)
+    live, freed, sizes = {}, [], []
+
+    def alloc(nbytes):
+        p = torch.cuda.caching_allocator_alloc(nbytes, 0)
+        assert p % 256 == 0
+        live[p] = nbytes
+        sizes.append(nbytes)
+        return p
+
+    def free(p):
+        freed.append(p)
+        assert live.pop(p, None) is not None, "free of a pointer the library was not given"
+        torch.cuda.caching_allocator_delete(p)
+
+    opt = dict(dense_rows=100, dense_alias_min_count=int(np.bincount(words).max()) + 1) if hybrid else {}
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=3, dev_alloc=alloc,
+                    dev_free=free, **opt)
+    o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=3,
+                          dense_alias_min_count=opt.get("dense_alias_min_count", 0))
+    n_init = len(sizes)
+    assert n_init > 10 and len(freed) > 0  # the set-up's temporaries went back already
+    for m in (2, 4, 2):
+        g.build_alias()
+        o.build_alias()
+        g.sweep(m)
+        o.sweep(m)
+        g.rebuild_counts()
+        o.rebuild_counts()
+    check_state(g, o, docs=range(0, 300, 29), words=range(0, cfg.V, 97), tag="caller allocator")
+    assert len(sizes) > n_init  # the sweeps' records are allocated on first use
+    g.close()
+    o.close()
+    assert not live, "%d buffers were not returned at lda_destroy" % len(live)
+
+    # an allocator that fails: lda_init reports LDA_ERR_OOM and returns what it had taken
+    budget = [3]
+
+    def failing(nbytes):
+        if budget[0] == 0:
+            return 0
+        budget[0] -= 1
+        return alloc(nbytes)
+
+    with pytest.raises(lda_mod.LdaError) as e:
+        lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=3, dev_alloc=failing,
+                    dev_free=free)
+    assert e.value.code == lda_mod.LDA_ERR_OOM
+    assert not live
+
+
 def test_chain_shape_changes_between_sweeps(lda_mod, oracle_mod):
     """The two-pass sweep keeps the next sweep's doc proposals from the previous doc pass;
     they must be redrawn when the number of steps changes, after lda_set_z (other
