@@ -614,6 +614,129 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
     }
 }
 
+// What a thread holds of its T tokens of one tile before the tile is staged.
+template <int T, int R>
+struct TileTokens {
+    int32_t d0, d1, tok0, ntok;  // uniform over the workgroup
+    bool valid;                  // uniform: a tile this kernel handles
+    uint32_t g[T];
+    int32_t wp[T], idx[T], z0[T], dl[T], r[T][R];
+    bool live[T];
+};
+
+// first half of a tile's loads: the tile's bounds and, per token, the word-major position
+template <int T, int R>
+__device__ __forceinline__ void tile_issue_positions(const SplitArgs& A, int32_t c, TileTokens<T, R>& t)
+{
+    t.valid = c < A.n_chunks;
+    if (!t.valid) return;
+    t.d0 = A.chunk_doc[c];
+    t.d1 = A.chunk_doc[c + 1];
+    t.tok0 = A.doff[t.d0];
+    t.ntok = A.doff[t.d1] - t.tok0;
+    // nothing / a long document (the long-document kernel's)
+    t.valid = !(t.ntok == 0 || (t.d1 - t.d0 == 1 && t.ntok > A.max_doc_tokens));
+    if (!t.valid) return;
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        // lanes past the end of the tile redo its last token and drop the result
+        int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
+        t.live[u] = i < t.ntok;
+        if (!t.live[u]) i = t.ntok - 1;
+        t.idx[u] = i;
+        t.g[u] = (uint32_t)(t.tok0 + i);
+        t.wp[u] = __builtin_nontemporal_load(&A.wpos[t.g[u]]);
+    }
+}
+
+// second half: the word-pass records (one random line per token), snapshot topics, documents
+template <int T, int R, int RS>
+__device__ __forceinline__ void tile_issue_records(const SplitArgs& A, TileTokens<T, R>& t)
+{
+    if (!t.valid) return;
+#pragma unroll
+    for (int u = 0; u < T; ++u) load_ints<R>(A.rec + ((size_t)t.wp[u] << RS), t.r[u]);
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        t.z0[u] = __builtin_nontemporal_load(&A.z[t.g[u]]);
+        t.dl[u] = (int32_t)__builtin_nontemporal_load(&A.tokdoc[t.g[u]]);
+    }
+}
+
+// Stage the tile as load_doc_tile does (doc_tile.hpp: same LDS layout, same tables) but keep
+// what each thread learns about its own tokens in registers -- the thread that inserts a
+// token into its document's table is the one that runs its chain --, run the chains, write
+// the new assignment, and from it draw the doc proposals of the next sweep.
+template <int NW, int ND, int T>
+__device__ __forceinline__ void tile_process(const SplitArgs& A, int32_t* smem,
+                                             const int32_t* __restrict__ nk,
+                                             const TileTokens<T, Chain<NW, ND>::R>& t)
+{
+    using C = Chain<NW, ND>;
+    DocTile tile;
+    tile.zs = reinterpret_cast<uint32_t*>(smem);
+    tile.tab = reinterpret_cast<uint32_t*>(smem + A.cap_tokens);
+    tile.sdoff = smem + 3 * (size_t)A.cap_tokens;
+    tile.nd = t.d1 - t.d0;
+    tile.tok0 = t.tok0;
+    tile.ntok = t.ntok;
+    int32_t nd0[T], s[T];
+    uint32_t slot[T];
+    for (int32_t i = threadIdx.x; i <= tile.nd; i += blockDim.x) tile.sdoff[i] = A.doff[t.d0 + i] - t.tok0;
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (t.live[u]) {
+            tile.zs[t.idx[u]] = (uint32_t)t.z0[u];
+            reinterpret_cast<uint2*>(tile.tab)[t.idx[u]] = make_uint2(kEmptySlot, kEmptySlot);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (t.live[u]) {
+            slot[u] = tile.table(t.dl[u]).insert(t.z0[u]);
+            tile.zs[t.idx[u]] = (uint32_t)t.z0[u] | (slot[u] << kTopicBits);  // own element only
+        }
+    }
+    __syncthreads();
+    TileDoc doc[T];
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        const int32_t b = tile.sdoff[t.dl[u]];
+        doc[u].L = tile.sdoff[t.dl[u] + 1] - b;
+        doc[u].tab = tile.table(t.dl[u]);
+        doc[u].zs = tile.zs + b;
+        if (!t.live[u]) slot[u] = tile.zs[t.idx[u]] >> kTopicBits;  // a clone of the last token
+        nd0[u] = doc[u].tab.count_at(slot[u]);
+    }
+    doc_pass_chains<NW, ND, T>(A, doc, t.g, t.r, t.z0, nd0, nk, s);
+#pragma unroll
+    for (int u = 0; u < T; ++u)
+        if (t.live[u]) __builtin_nontemporal_store(s[u], &A.znew[t.g[u]]);
+    // the tile's new assignment replaces the staged snapshot; from it, the doc proposals
+    // of the next sweep
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u)
+        if (t.live[u]) tile.zs[t.idx[u]] = (uint32_t)s[u];
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        if (!t.live[u]) continue;
+        int32_t row[1 + ND];
+        row[0] = s[u];
+#pragma unroll
+        for (int k = 0; k < ND; ++k) {
+            uint32_t x[4];
+            philox4x32_10(t.g[u], 0u, A.sweep + 1u, (uint32_t)C::doc_step(k), A.seed_lo, A.seed_hi, x);
+            const uint32_t* zs = doc[u].zs;
+            row[1 + k] = doc_proposal(x[0], x[1], doc[u].L, A.K, A.alphabar,
+                                      [&](uint32_t j) { return (int32_t)zs[j]; });
+        }
+        store_zt<ND>(A, (size_t)t.wp[u], row);
+    }
+}
+
 // One workgroup per document tile; a thread runs the chains of up to T of its tokens,
 // interleaved.  Chains of up to two steps with up to two tokens per thread are compiled for
 // a fixed number of waves per SIMD (7 in blocks of up to 256 threads, 6 up to 768): one more
@@ -638,94 +761,12 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && NW + ND <= 2) ? (MAXB <= 256 ? 7 :
     }
     const int32_t c = xcd_contiguous(A.n_chunks);
     if (c >= A.n_chunks) return;
-    const int32_t d0 = A.chunk_doc[c], d1 = A.chunk_doc[c + 1];
-    const int32_t ntok = A.doff[d1] - A.doff[d0];
-    if (ntok == 0 || (d1 - d0 == 1 && ntok > A.max_doc_tokens)) return;  // nothing / a long document
     // the word-pass records do not depend on the tile: their gather (one random line per
     // token) is issued first and overlaps the staging of the documents
-    const int32_t tok0 = A.doff[d0];
-    uint32_t g[T];
-    int32_t wp[T], s[T], idx[T], r[T][C::R];
-    bool live[T];
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        // lanes past the end of the tile redo its last token and drop the result
-        int32_t i = (int32_t)threadIdx.x + u * (int32_t)blockDim.x;
-        live[u] = i < ntok;
-        if (!live[u]) i = ntok - 1;
-        idx[u] = i;
-        g[u] = (uint32_t)(tok0 + i);
-        wp[u] = __builtin_nontemporal_load(&A.wpos[g[u]]);
-    }
-#pragma unroll
-    for (int u = 0; u < T; ++u) load_ints<C::R>(A.rec + ((size_t)wp[u] << C::rec_shift), r[u]);
-    // Stage the documents as load_doc_tile does (doc_tile.hpp: same LDS layout, same tables),
-    // but keep what each thread learns about its own tokens in registers: the thread that
-    // inserts a token into its document's table is the one that runs its chain.
-    DocTile tile;
-    tile.zs = reinterpret_cast<uint32_t*>(smem);
-    tile.tab = reinterpret_cast<uint32_t*>(smem + A.cap_tokens);
-    tile.sdoff = smem + 3 * (size_t)A.cap_tokens;
-    tile.nd = d1 - d0;
-    tile.tok0 = tok0;
-    tile.ntok = ntok;
-    int32_t z0[T], dl[T], nd0[T];
-    uint32_t slot[T];
-    for (int32_t i = threadIdx.x; i <= tile.nd; i += blockDim.x) tile.sdoff[i] = A.doff[d0 + i] - tok0;
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        z0[u] = __builtin_nontemporal_load(&A.z[g[u]]);
-        dl[u] = (int32_t)__builtin_nontemporal_load(&A.tokdoc[g[u]]);
-        if (live[u]) {
-            tile.zs[idx[u]] = (uint32_t)z0[u];
-            reinterpret_cast<uint2*>(tile.tab)[idx[u]] = make_uint2(kEmptySlot, kEmptySlot);
-        }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        if (live[u]) {
-            slot[u] = tile.table(dl[u]).insert(z0[u]);
-            tile.zs[idx[u]] = (uint32_t)z0[u] | (slot[u] << kTopicBits);  // own element only
-        }
-    }
-    __syncthreads();
-    TileDoc doc[T];
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        const int32_t b = tile.sdoff[dl[u]];
-        doc[u].L = tile.sdoff[dl[u] + 1] - b;
-        doc[u].tab = tile.table(dl[u]);
-        doc[u].zs = tile.zs + b;
-        if (!live[u]) slot[u] = tile.zs[idx[u]] >> kTopicBits;  // a clone of the last token
-        nd0[u] = doc[u].tab.count_at(slot[u]);
-    }
-    doc_pass_chains<NW, ND, T>(A, doc, g, r, z0, nd0, nk, s);
-#pragma unroll
-    for (int u = 0; u < T; ++u)
-        if (live[u]) __builtin_nontemporal_store(s[u], &A.znew[g[u]]);
-    // the tile's new assignment replaces the staged snapshot; from it, the doc proposals
-    // of the next sweep
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < T; ++u)
-        if (live[u]) tile.zs[idx[u]] = (uint32_t)s[u];
-    __syncthreads();
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        if (!live[u]) continue;
-        int32_t row[1 + ND];
-        row[0] = s[u];
-#pragma unroll
-        for (int k = 0; k < ND; ++k) {
-            uint32_t x[4];
-            philox4x32_10(g[u], 0u, A.sweep + 1u, (uint32_t)C::doc_step(k), A.seed_lo, A.seed_hi, x);
-            const uint32_t* zs = doc[u].zs;
-            row[1 + k] = doc_proposal(x[0], x[1], doc[u].L, A.K, A.alphabar,
-                                      [&](uint32_t j) { return (int32_t)zs[j]; });
-        }
-        store_zt<ND>(A, (size_t)wp[u], row);
-    }
+    TileTokens<T, C::R> t;
+    tile_issue_positions<T, C::R>(A, c, t);
+    tile_issue_records<T, C::R, C::rec_shift>(A, t);
+    if (t.valid) tile_process<NW, ND, T>(A, smem, nk, t);
 }
 
 template <int NW, int ND>
