@@ -177,6 +177,14 @@ def main():
         for _ in range(3):
             torch.add(src, 1.0, out=dst)   # one kernel: 2^30 bytes in, 2^30 bytes out
         torch.cuda.synchronize()
+        # the same kernel timed: what a plain streaming copy reaches on this device
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            torch.add(src, 1.0, out=dst)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9
         del src, dst
 
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
@@ -244,6 +252,8 @@ def main():
         },
     }
     g.close()
+    if args.calibrate_copy:
+        out["config"]["streaming_copy_GBs"] = copy_gbs
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_docs or {"c1": 1000, "c2": 60000, "c3": 600000}[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample,
