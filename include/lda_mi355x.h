@@ -80,7 +80,12 @@ typedef struct lda_options {
     int32_t rebuild_tile_tokens;   /* tuning: tokens per count-rebuild tile; 0: default */
     int32_t time_sweep_passes;     /* 1: lda_sweep records HIP events around its two passes on the
                                       context's stream (read them with lda_sweep_pass_ms) */
-    int32_t reserved[8];           /* must be zero */
+    int32_t record_bucket_tokens;  /* tuning: the per-token records the two passes of a sweep
+                                      exchange are ordered by buckets of this many consecutive
+                                      tokens (a power of two), inside a bucket by word; 0: default
+                                      (2^22 when every n_kw row is dense, else one bucket);
+                                      -1: one bucket (plain word order) */
+    int32_t reserved[7];           /* must be zero */
 } lda_options;
 
 /*

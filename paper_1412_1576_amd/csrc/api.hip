@@ -74,7 +74,7 @@ void dev_free(lda_ctx* c, T*& p)
 void free_all(lda_ctx* c)
 {
     dev_free(c, c->d_word); dev_free(c, c->d_doff); dev_free(c, c->d_z); dev_free(c, c->d_znew);
-    dev_free(c, c->d_gid); dev_free(c, c->d_wpos); dev_free(c, c->d_zt); dev_free(c, c->d_rec);
+    dev_free(c, c->d_gid); dev_free(c, c->d_wpos); dev_free(c, c->d_xmap); dev_free(c, c->d_zt); dev_free(c, c->d_rec);
     dev_free(c, c->d_row_items); dev_free(c, c->d_mix_items); dev_free(c, c->d_gather_pieces);
     dev_free(c, c->d_sort_keys);
     dev_free(c, c->d_sp_wloc); dev_free(c, c->d_sp_keys); dev_free(c, c->d_sp_sorted); dev_free(c, c->d_sp_runlen);
@@ -335,8 +335,11 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         o.sweep_block_threads < 0 || o.rebuild_tile_tokens < 0 || o.time_sweep_passes < 0 ||
         o.time_sweep_passes > 1)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 7; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
+    if (o.record_bucket_tokens < -1 ||
+        (o.record_bucket_tokens > 0 && (o.record_bucket_tokens & (o.record_bucket_tokens - 1)) != 0))
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: record_bucket_tokens must be a power of two");
     if ((o.dev_alloc == nullptr) != (o.dev_free == nullptr))
         return fail(nullptr, LDA_ERR_ARG, "lda_init: dev_alloc and dev_free must be set together");
     // The kernels of the all-dense case keep a whole row or table in LDS; beyond their K the
@@ -360,6 +363,15 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     c->opt = o;
     c->hybrid = hybrid;
     c->H = H;
+    {   // order of the records the sweep's two passes exchange (layout.hip, launch_layout)
+        int32_t bucket = o.record_bucket_tokens;
+        if (bucket == 0) bucket = (H == V) ? (1 << 22) : -1;
+        c->record_bucket_shift = 0;
+        if (bucket > 0 && (int64_t)bucket < N)
+            while ((1 << c->record_bucket_shift) < bucket) ++c->record_bucket_shift;
+        else
+            c->record_bucket_shift = -1;  // one bucket
+    }
     c->stream = reinterpret_cast<hipStream_t>(o.hip_stream);
 
     // sweep tiling parameters (LDS: 12 bytes per token + 4 per document).  A packed n_kd

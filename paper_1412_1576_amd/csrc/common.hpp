@@ -54,7 +54,11 @@ struct lda_ctx {
     int32_t* d_znew = nullptr;  // [N] next assignment
     // word-major view
     int32_t* d_gid = nullptr;   // [N] CSR position of the p-th token in word-major order
-    int32_t* d_wpos = nullptr;  // [N] word-major position of token g (inverse of gid)
+    int32_t* d_wpos = nullptr;  // [N] position of token g's records in zt / rec: its word-major
+                                //     position (inverse of gid), mapped through d_xmap if set
+    int32_t* d_xmap = nullptr;  // [N] word-major position -> record position (NULL: identity)
+    int32_t record_bucket_shift = -1;  // records ordered by (CSR position >> shift, word-major
+                                       // position); -1: by word-major position alone
     // Word-major token records of 2^zt_shift ints.  Fields: the token's z, then the topic that
     // doc step i of the coming sweep proposes for it (when td_valid); one int per field, or,
     // with zt_pack16 (K <= 65536), two 16-bit fields per int.  The z field is the low

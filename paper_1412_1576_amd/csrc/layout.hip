@@ -70,6 +70,24 @@ __global__ __launch_bounds__(256) void invert_kernel(const int32_t* __restrict__
         wpos[gid[p]] = (int32_t)p;
 }
 
+// keys[p] = bucket of the token at word-major position p (its CSR position >> shift)
+__global__ __launch_bounds__(256) void bucket_keys_kernel(const int32_t* __restrict__ gid, int64_t n,
+                                                          int shift, int32_t* __restrict__ keys)
+{
+    for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < n;
+         p += (int64_t)gridDim.x * blockDim.x)
+        keys[p] = gid[p] >> shift;
+}
+
+// wpos[g] = xmap[wpos[g]]
+__global__ __launch_bounds__(256) void compose_kernel(int32_t* __restrict__ wpos, int64_t n,
+                                                      const int32_t* __restrict__ xmap)
+{
+    for (int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; g < n;
+         g += (int64_t)gridDim.x * blockDim.x)
+        wpos[g] = xmap[wpos[g]];
+}
+
 // n_k[k] = number of entries equal to k in the ascending array `sorted`
 __global__ __launch_bounds__(256) void nk_from_sorted_kernel(const int32_t* __restrict__ sorted,
                                                              int64_t n, int32_t K,
@@ -115,11 +133,14 @@ __global__ __launch_bounds__(256) void sparse_keys_kernel(const int32_t* __restr
                                                           uint32_t zmask,
                                                           const uint32_t* __restrict__ wloc,
                                                           int64_t p0, int64_t n, int32_t tb,
+                                                          const int32_t* __restrict__ xmap,
                                                           uint64_t* __restrict__ keys)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x)
-        keys[i] = ((uint64_t)wloc[i] << tb) | (uint64_t)((uint32_t)zt[(size_t)(p0 + i) << sh] & zmask);
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const size_t q = xmap ? (size_t)xmap[p0 + i] : (size_t)(p0 + i);
+        keys[i] = ((uint64_t)wloc[i] << tb) | (uint64_t)((uint32_t)zt[q << sh] & zmask);
+    }
 }
 
 // first[wl] = index of the first run (distinct key) of word H + wl, wl = 0..n_words
@@ -277,7 +298,7 @@ int launch_sparse_lists_by_sort(lda_ctx* c)
     }
     if (n > 0) {
         hipLaunchKernelGGL(sparse_keys_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream, c->d_zt,
-                           c->zt_shift, c->zt_mask, c->d_sp_wloc, p0, n, tb, c->d_sp_keys);
+                           c->zt_shift, c->zt_mask, c->d_sp_wloc, p0, n, tb, c->d_xmap, c->d_sp_keys);
         LDA_HIP(c, hipGetLastError());
         size_t bytes = c->sp_tmp_bytes;
         LDA_HIP(c, rocprim::radix_sort_keys(c->d_sp_tmp, bytes, c->d_sp_keys, c->d_sp_sorted, (size_t)n,
@@ -306,6 +327,71 @@ int launch_sparse_lists_by_sort(lda_ctx* c)
     }
     return LDA_OK;
 }
+
+namespace {
+
+// Record order of the sweep's exchange.  The word pass writes one record per token and reads
+// one; the doc pass gathers and scatters them.  In plain word-major order the records of a
+// rare word are spread over the whole array, so the doc pass's access to them is a miss in
+// every cache.  Ordering the records by buckets of 2^shift consecutive tokens of the corpus
+// (inside a bucket by word-major position) confines the doc pass, which walks the corpus in
+// order, to one bucket's records at a time -- a window of some tens of megabytes that the
+// memory-side cache holds -- while the word pass still meets the records of a word in
+// ascending order, now as one run per bucket.
+//   xmap[p] = rank of word-major position p under the key (gid[p] >> shift, p)
+//   wpos[g] = xmap[wpos[g]]
+int build_record_order(lda_ctx* c)
+{
+    const int64_t N = c->N;
+    const int shift = c->record_bucket_shift;
+    int32_t *keys = nullptr, *keys_sorted = nullptr, *pos = nullptr, *pos_sorted = nullptr;
+    void* tmp = nullptr;
+    auto release = [&]() {
+        device_free(c, keys);
+        device_free(c, keys_sorted);
+        device_free(c, pos);
+        device_free(c, pos_sorted);
+        device_free(c, tmp);
+    };
+    int rc = device_malloc(c, &keys, (size_t)N, "record order");
+    if (rc == LDA_OK) rc = device_malloc(c, &keys_sorted, (size_t)N, "record order");
+    if (rc == LDA_OK) rc = device_malloc(c, &pos, (size_t)N, "record order");
+    if (rc == LDA_OK) rc = device_malloc(c, &pos_sorted, (size_t)N, "record order");
+    if (rc == LDA_OK) rc = device_malloc(c, &c->d_xmap, (size_t)N, "record order");
+    if (rc != LDA_OK) {
+        release();
+        return rc;
+    }
+    hipLaunchKernelGGL(bucket_keys_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_gid, N,
+                       shift, keys);
+    hipLaunchKernelGGL(iota_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, pos, N);
+    int end_bit = 1;
+    while (end_bit < 31 && (1LL << end_bit) < ((long long)(N - 1) >> shift) + 1) ++end_bit;
+    size_t tmp_bytes = 0;
+    // stable: inside a bucket the word-major positions stay ascending
+    hipError_t e = rocprim::radix_sort_pairs(nullptr, tmp_bytes, keys, keys_sorted, pos, pos_sorted,
+                                             (size_t)N, 0u, (unsigned)end_bit, c->stream);
+    if (e == hipSuccess && (rc = device_malloc(c, &tmp, tmp_bytes, "record order")) != LDA_OK) {
+        release();
+        return rc;
+    }
+    if (e == hipSuccess)
+        e = rocprim::radix_sort_pairs(tmp, tmp_bytes, keys, keys_sorted, pos, pos_sorted, (size_t)N, 0u,
+                                      (unsigned)end_bit, c->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(invert_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, pos_sorted, N,
+                           c->d_xmap);
+        hipLaunchKernelGGL(compose_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_wpos, N,
+                           c->d_xmap);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    release();
+    if (e != hipSuccess) return fail(c, LDA_ERR_HIP, "record order: %s", hipGetErrorString(e));
+    return LDA_OK;
+}
+
+}  // namespace
 
 int launch_layout(lda_ctx* c, const int32_t* /*h_word*/)
 {
@@ -350,6 +436,10 @@ int launch_layout(lda_ctx* c, const int32_t* /*h_word*/)
     hipLaunchKernelGGL(invert_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_gid, N,
                        c->d_wpos);
     LDA_HIP(c, hipGetLastError());
+    if (c->record_bucket_shift >= 0) {
+        const int rc2 = build_record_order(c);
+        if (rc2 != LDA_OK) return rc2;
+    }
     hipLaunchKernelGGL(init_z_kernel, dim3(grid_for(N, 256)), dim3(256), 0, c->stream, c->d_z, N,
                        c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
     LDA_HIP(c, hipGetLastError());

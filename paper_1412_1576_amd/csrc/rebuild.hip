@@ -9,6 +9,7 @@
 // n_k: an LDS-privatised histogram of z over all tokens (a radix sort of z for very large K,
 // layout.hip).
 #include "common.hpp"
+#include "xcd.hpp"
 
 namespace lda {
 
@@ -23,7 +24,6 @@ namespace {
 // token range and walks it in order, so that the partially written lines of the
 // frequent words stay in that XCD's L2 until they are full instead of being
 // written back piecemeal by eight caches.
-constexpr int kXcds = 8;
 constexpr int kScatterPerThread = 1;
 constexpr int kScatterBlock = 1024;
 
@@ -47,7 +47,10 @@ __global__ __launch_bounds__(1024) void scatter_wm_kernel(const int32_t* __restr
 }
 
 // blockIdx.x: tile; blockIdx.y: range of `span` topics (one range when the row fits LDS)
+constexpr int32_t kTileRun = 32;
+
 __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __restrict__ tiles,
+                                                         int32_t n_tiles,
                                                          const int32_t* __restrict__ zw,
                                                          int32_t sh, uint32_t zmask, int32_t K,
                                                          int32_t span,
@@ -55,11 +58,16 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
                                                          const uint32_t* __restrict__ sp_off,
                                                          int32_t* __restrict__ sp_topic,
                                                          int32_t* __restrict__ sp_count,
-                                                         int32_t* __restrict__ sp_nnz)
+                                                         int32_t* __restrict__ sp_nnz,
+                                                         const int32_t* __restrict__ xmap)
 {
     extern __shared__ int32_t hist[];
     __shared__ uint32_t wcnt[16];
-    const RebuildTile t = tiles[blockIdx.x];
+    // runs of consecutive tiles (neighbouring words) share an XCD and with it the lines of
+    // the records they read
+    const int32_t ti = xcd_runs(kTileRun);
+    if (ti >= n_tiles) return;
+    const RebuildTile t = tiles[ti];
     const int32_t k0 = (int32_t)blockIdx.y * span;
     const int32_t nk_r = ((k0 + span < K) ? k0 + span : K) - k0;
     const int tid = threadIdx.x, nt = blockDim.x;
@@ -69,15 +77,19 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
         const uint32_t r = ((uint32_t)rec & zmask) - (uint32_t)k0;
         if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
     };
+    auto at = [&](int32_t p) -> size_t { return xmap ? (size_t)xmap[p] : (size_t)p; };
     int32_t p = t.p0 + tid;
     for (; p + 3 * nt < t.p1; p += 4 * nt) {  // four loads in flight per thread
+        size_t q[4];
         int32_t rec[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) rec[u] = __builtin_nontemporal_load(&zw[(size_t)(p + u * nt) << sh]);
+        for (int u = 0; u < 4; ++u) q[u] = at(p + u * nt);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) rec[u] = __builtin_nontemporal_load(&zw[q[u] << sh]);
 #pragma unroll
         for (int u = 0; u < 4; ++u) count(rec[u]);
     }
-    for (; p < t.p1; p += nt) count(zw[(size_t)p << sh]);
+    for (; p < t.p1; p += nt) count(zw[at(p) << sh]);
     __syncthreads();
     int32_t* __restrict__ row = nkw + (size_t)t.w * (size_t)K + (size_t)k0;
     if (t.multi == 1) {
@@ -217,10 +229,11 @@ int launch_dense_rows(lda_ctx* c)
                            c->d_multi_words, K, c->d_nkw);
         LDA_HIP(c, hipGetLastError());
     }
-    hipLaunchKernelGGL(nkw_tiles_kernel, dim3(c->n_tiles, (K + span - 1) / span),
-                       dim3(span <= 512 ? 256 : (span <= 16384 ? 512 : 1024)), lds, c->stream, c->d_tiles, c->d_zt,
+    hipLaunchKernelGGL(nkw_tiles_kernel, dim3(xcd_runs_grid(c->n_tiles, kTileRun), (K + span - 1) / span),
+                       dim3(span <= 512 ? 256 : (span <= 16384 ? 512 : 1024)), lds, c->stream, c->d_tiles,
+                       c->n_tiles, c->d_zt,
                        c->zt_shift, c->zt_mask, K, span,
-                       c->d_nkw, c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz);
+                       c->d_nkw, c->d_sp_off, c->d_sp_topic, c->d_sp_count, c->d_sp_nnz, c->d_xmap);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }

@@ -28,12 +28,12 @@
 #include "common.hpp"
 #include "doc_tile.hpp"
 #include "word_side.hpp"
+#include "xcd.hpp"
 
 namespace lda {
 
 namespace {
 
-constexpr int kXcds = 8;
 constexpr int32_t kRowItemTokens = 32768;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
 constexpr int32_t kMixRowTopics = 16384;   // largest K whose n_kw row a mixture item keeps in LDS
@@ -107,6 +107,7 @@ struct SplitArgs {
     const int32_t* chunk_doc;
     const uint8_t* tokdoc;
     const int32_t* wpos;
+    const int32_t* xmap;  // word-major position -> record position (NULL: identity)
     const int32_t* gid;
     const int32_t* woff;
     const int32_t* nkw;
@@ -148,7 +149,13 @@ struct SplitArgs {
 // when every topic fits 16 bits, two fields per int; rounded up to a power of two
 constexpr int zt_record_shift(int nd, bool pack16) { return pow2_shift(pack16 ? (2 + nd) / 2 : 1 + nd); }
 
-// v[0] = z, v[1 + i] = the topic doc step i proposes, of the token at word-major position p
+// record position of the token at word-major position p
+__device__ __forceinline__ size_t record_at(const SplitArgs& A, int32_t p)
+{
+    return A.xmap ? (size_t)A.xmap[p] : (size_t)p;
+}
+
+// v[0] = z, v[1 + i] = the topic doc step i proposes, of the token whose records are at p
 template <int ND>
 __device__ __forceinline__ void load_zt(const SplitArgs& A, size_t p, int32_t (&v)[1 + ND])
 {
@@ -187,33 +194,6 @@ __device__ __forceinline__ void store_zt(const SplitArgs& A, size_t p, const int
         for (int k = 0; k <= ND; ++k) w[k] = v[k];
         store_ints<W>(A.zt + p * W, w);
     }
-}
-
-// Workgroups are dealt to the 8 XCDs round-robin.  Handing each XCD one contiguous run of
-// the items keeps neighbouring items -- which touch neighbouring word-major records -- in
-// one L2.  Returns an index that may lie past the last item.
-__device__ __forceinline__ int32_t xcd_contiguous(int32_t n_items)
-{
-    const int32_t per = (n_items + kXcds - 1) / kXcds;
-    return (int32_t)(blockIdx.x % kXcds) * per + (int32_t)(blockIdx.x / kXcds);
-}
-
-unsigned xcd_grid(int32_t n_items) { return (unsigned)((n_items + kXcds - 1) / kXcds * kXcds); }
-
-// The word pass's work lists are in word order, and the cost of an item depends on its
-// word's class (frequent words are served from LDS or L2, rare ones miss), so contiguous
-// eighths would leave the XCDs unevenly loaded.  Runs of `run` consecutive items are dealt
-// to the XCDs in turn instead: neighbours still share an L2, every XCD sees every class.
-__device__ __forceinline__ int32_t xcd_runs(int32_t run)
-{
-    const int32_t xcd = (int32_t)(blockIdx.x % kXcds), seq = (int32_t)(blockIdx.x / kXcds);
-    return ((seq / run) * kXcds + xcd) * run + seq % run;
-}
-
-unsigned xcd_runs_grid(int32_t n_items, int32_t run)
-{
-    const int32_t runs = (n_items + run - 1) / run;
-    return (unsigned)((runs + kXcds - 1) / kXcds * kXcds * run);
 }
 
 constexpr int32_t kRowItemRun = 8, kMixItemRun = 16, kPieceRun = 64;
@@ -291,6 +271,7 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     constexpr int U = 4;
     for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
         int32_t p[U], zt[U][1 + ND];
+        size_t q[U];
         uint32_t g[U];
         bool live[U];
 #pragma unroll
@@ -299,7 +280,8 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
             live[u] = i < it.z;
             if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
             p[u] = it.y + i;
-            load_zt<ND>(A, (size_t)p[u], zt[u]);
+            q[u] = record_at(A, p[u]);
+            load_zt<ND>(A, q[u], zt[u]);
             g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
         }
 #pragma unroll
@@ -322,7 +304,7 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
             }
 #pragma unroll
             for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[u][1 + k]];
-            if (live[u]) store_ints<C::R>(A.rec + ((size_t)p[u] << C::rec_shift), out);
+            if (live[u]) store_ints<C::R>(A.rec + (q[u] << C::rec_shift), out);
         }
     }
 }
@@ -361,7 +343,8 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
             const int32_t p = pc.z + i;
             const int32_t w = pc.x + piece_word(soff, nwords, p);
             int32_t zt[1 + ND], out[C::R];
-            load_zt<ND>(A, (size_t)p, zt);
+            const size_t q = record_at(A, p);
+            load_zt<ND>(A, q, zt);
 #pragma unroll
             for (int k = 0; k < C::R; ++k) out[k] = 0;
             const size_t wk = (size_t)w * (size_t)K;
@@ -383,7 +366,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
             }
 #pragma unroll
             for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
-            store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+            store_ints<C::R>(A.rec + (q << C::rec_shift), out);
         }
     } else {
         constexpr int U = 2;
@@ -391,6 +374,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
         if constexpr (NW > 0) bt = load_beta_table(A);
         for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
             int32_t p[U], zt[U][1 + ND], out[U][C::R];
+            size_t q[U];
             bool live[U];
             WordSide wv[U];
             uint32_t g[U];
@@ -401,7 +385,8 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
                 live[u] = i < pc.w;
                 if (!live[u]) i = pc.w - 1;
                 p[u] = pc.z + i;
-                load_zt<ND>(A, (size_t)p[u], zt[u]);
+                q[u] = record_at(A, p[u]);
+                load_zt<ND>(A, q[u], zt[u]);
                 g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
                 wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
 #pragma unroll
@@ -443,7 +428,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
 #pragma unroll
                 for (int k = 0; k < ND; ++k)
                     out[u][C::rec_doc(k)] = nkw_probe_finish<STORE>(wv[u], zt[u][1 + k], pr[u][1 + k]);
-                if (live[u]) store_ints<C::R>(A.rec + ((size_t)p[u] << C::rec_shift), out[u]);
+                if (live[u]) store_ints<C::R>(A.rec + (q[u] << C::rec_shift), out[u]);
             }
         }
     }
@@ -478,7 +463,8 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
     for (int32_t i = tid; i < it.z; i += nt) {
         const int32_t p = it.y + i;
         int32_t zt[1 + ND], out[C::R];
-        load_zt<ND>(A, (size_t)p, zt);
+        const size_t q = record_at(A, p);
+        load_zt<ND>(A, q, zt);
 #pragma unroll
         for (int k = 0; k < C::R; ++k) out[k] = 0;
         out[0] = row[zt[0]];
@@ -498,7 +484,7 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
         }
 #pragma unroll
         for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
-        store_ints<C::R>(A.rec + ((size_t)p << C::rec_shift), out);
+        store_ints<C::R>(A.rec + (q << C::rec_shift), out);
     }
 }
 
@@ -1041,7 +1027,7 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
                                    c->td_nd == nd));
     SplitArgs A{};
     A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff; A.chunk_doc = c->d_chunk_doc;
-    A.tokdoc = c->d_tokdoc; A.wpos = c->d_wpos; A.gid = c->d_gid; A.woff = c->d_woff;
+    A.tokdoc = c->d_tokdoc; A.wpos = c->d_wpos; A.xmap = c->d_xmap; A.gid = c->d_gid; A.woff = c->d_woff;
     A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias; A.cap = c->d_cap;
     A.zt = c->d_zt; A.zt_pack16 = c->zt_pack16 ? 1 : 0; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
     A.n_chunks = c->n_chunks; A.n_row_items = c->n_row_items; A.n_pieces = c->n_gather_pieces;

@@ -37,7 +37,7 @@ def test_exports_every_declared_symbol(lib):
 
 def test_options_struct_layout():
     from paper_1412_1576_amd import lda
-    # stream, the three allocator fields, 7 int32, 8 reserved int32
+    # stream, the three allocator fields, 8 int32, 7 reserved int32
     assert C.sizeof(lda.lda_options) == 4 * 8 + 15 * 4 + 4  # padded to 8-byte alignment
     assert lda.lda_options.dev_alloc.offset == 8
     assert lda.lda_options.dense_rows.offset == 32
@@ -66,6 +66,7 @@ def test_bad_arguments_are_rejected_on_the_host(lib):
     assert init(doff=np.array([0, 3, 2], np.int64))[0] == lda.LDA_ERR_ARG
     assert init(doff=np.array([0, 0, 0], np.int64))[0] == lda.LDA_ERR_ARG  # empty corpus
     assert init(proposal_mode=3)[0] == lda.LDA_ERR_ARG
+    assert init(record_bucket_tokens=1000)[0] == lda.LDA_ERR_ARG  # not a power of two
     only_alloc = lda.DEV_ALLOC(lambda nbytes, user: None)
     assert init(dev_alloc=only_alloc)[0] == lda.LDA_ERR_ARG  # dev_free missing
     rc, msg = init(K=0)

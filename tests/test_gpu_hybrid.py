@@ -82,6 +82,14 @@ def test_hybrid_small(lda_mod, oracle_mod):
     assert dense_alias[:150].any() and not dense_alias[:150].all()  # both kinds among dense rows
 
 
+def test_hybrid_record_buckets(lda_mod, oracle_mod):
+    """The bucketed record order on the hybrid store (not its default there)."""
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=600)
+    doff, words = corpus.make_corpus(cfg)
+    run_hybrid(lda_mod, oracle_mod, doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, 0, 3, 2,
+               dense_rows=150, docs=range(0, 600, 41), record_bucket_tokens=2048)
+
+
 def test_all_sparse_all_mixture(lda_mod, oracle_mod):
     """No dense row at all (the shape of one K = 10^6 model slice); the hottest words go
     through the scratch-row rebuild (more than 16384 tokens), the others through the LDS sorts."""

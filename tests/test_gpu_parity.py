@@ -222,6 +222,18 @@ def test_state_machine_and_checkpoint(lda_mod, oracle_mod):
     g.close(); h.close()
 
 
+@pytest.mark.parametrize("bucket", [-1, 64, 1024, 32768])
+@pytest.mark.parametrize("mh", [2, 3])
+def test_record_order(lda_mod, oracle_mod, bucket, mh):
+    """The records the word pass and the doc pass exchange, ordered by buckets of consecutive
+    tokens (many buckets, a few, a single partial one) or by word alone: same bits."""
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=500)
+    doff, words = corpus.make_corpus(cfg)
+    run_pair(lda_mod, oracle_mod, doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, 5, 3, mh,
+             docs=range(0, 500, 37), nkw_words=range(0, cfg.V, 41), alias_words=range(0, cfg.V, 53),
+             record_bucket_tokens=bucket)
+
+
 @pytest.mark.parametrize("hybrid", [False, True])
 def test_caller_allocator(lda_mod, oracle_mod, hybrid):
     """Every device buffer comes from the caller's allocator (here PyTorch's caching

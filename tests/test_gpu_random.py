@@ -1,8 +1,9 @@
 """GPU parity on seeded random configurations: corpus shape, K, store (all dense rows, head
 dense / tail sparse, all sparse), proposal form (dense tables, mixture below a random corpus
-frequency), number of MH steps changing from sweep to sweep, proposal mode and launch
-geometry are all drawn from the case's seed.  Every case compares z, n_k, sampled n_kw and
-n_kd rows and the log-likelihood with the oracle after every sweep (bit-exact / 1e-9).
+frequency), number of MH steps changing from sweep to sweep, proposal mode, launch geometry
+and the order of the records the two passes exchange are all drawn from the case's seed.
+Every case compares z, n_k, sampled n_kw and n_kd rows and the log-likelihood with the
+oracle after every sweep (bit-exact / 1e-9).
 """
 import numpy as np
 import pytest
@@ -76,6 +77,8 @@ def random_case(seed):
         opt["sweep_block_threads"] = int(rng.choice([64, 256, 512, 1024]))
     if rng.random() < 0.4:
         opt["rebuild_tile_tokens"] = int(rng.choice([64, 1000, 65536]))
+    if rng.random() < 0.5:
+        opt["record_bucket_tokens"] = int(rng.choice([-1, 64, 512, 8192]))
     steps = [int(x) for x in rng.integers(1, 6, 3)]
     alpha = float(rng.choice([0.01, 0.1, 1.0]))
     beta = float(rng.choice([0.01, 0.1]))
