@@ -53,7 +53,7 @@ def doc_pass_bytes_per_token(mh_steps: int) -> float:
 # fetched + written); keyed by (workload, mh_steps, dense_alias_min_count).  None where not
 # measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2, 10000): (17_920_249.3 * 2.000 + 12_494_336.2 * 1.000) * 1024.0,
+    ("c3", 2, 10000): (17_680_695.6 * 2.000 + 12_957_465.9 * 1.000) * 1024.0,
 }
 
 
@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--chunk-tokens", type=int, default=0)
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
+    ap.add_argument("--record-bucket-tokens", type=int, default=0, help="order of the records the "
+                    "sweep's passes exchange (lda_options.record_bucket_tokens); 0: default")
     ap.add_argument("--dense-alias-min-count", type=int, default=-1, help="c1-c3: words with "
                     "fewer tokens draw from the sparsified mixture word-proposal (Sec. 4.2) "
                     "instead of a dense K-bin table; -1 (default) = K; 0 = dense tables for "
@@ -144,7 +146,7 @@ def main():
     g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                 stream=stream.cuda_stream, sweep_chunk_tokens=args.chunk_tokens,
                 sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens,
-                time_sweep_passes=1, **hybrid)
+                time_sweep_passes=1, record_bucket_tokens=args.record_bucket_tokens, **hybrid)
     g.sync()
     t_init = time.perf_counter() - t0
 

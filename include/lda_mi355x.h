@@ -83,7 +83,8 @@ typedef struct lda_options {
     int32_t record_bucket_tokens;  /* tuning: the per-token records the two passes of a sweep
                                       exchange are ordered by buckets of this many consecutive
                                       tokens (a power of two), inside a bucket by word; 0: default
-                                      (2^22 when every n_kw row is dense, else one bucket);
+                                      (2^22 when every n_kw row is dense and the corpus has at
+                                      least 2^28 tokens, else one bucket);
                                       -1: one bucket (plain word order) */
     int32_t reserved[7];           /* must be zero */
 } lda_options;
