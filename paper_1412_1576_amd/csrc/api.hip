@@ -155,7 +155,7 @@ int upload(lda_ctx* c, T** dst, const std::vector<T>& v, const char* what)
 // pass over the row (needs h_wcount, h_wkind).
 bool list_from_rebuild(const lda_ctx* c, int32_t w)
 {
-    return c->hybrid && c->h_wkind[w] == 1 && c->h_wcount[w] <= c->rebuild_tile_tokens &&
+    return c->hybrid && (c->h_wkind[w] & 3) == 1 && c->h_wcount[w] <= c->rebuild_tile_tokens &&
            c->K <= max_rebuild_topics();
 }
 
@@ -169,7 +169,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->h_wkind.resize(V);
     c->h_sp_off.assign((size_t)V + 1, 0);
     c->h_hs_off.assign((size_t)V + 1, 0);
-    std::vector<int32_t> dense_alias, mix, sparse, compact, mixc[kMixClasses];
+    std::vector<int32_t> dense_alias, mix, sparse, compact, list_only, mixc[kMixClasses];
     std::vector<uint4> meta(2 * (size_t)V, make_uint4(0u, 0u, 0u, 0u));
     const int32_t lds_max = max_lds_table_entries();
     uint64_t list_total = 0, hash_total = 0;
@@ -182,7 +182,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
             return fail(c, LDA_ERR_ARG,
                         "lda_init: word %d (count %d) would draw from a dense table but has no dense "
                         "row; raise dense_alias_min_count or dense_rows", w, cw);
-        const uint8_t kind = (dense_row ? 1 : 0) | (dense_alias_w ? 2 : 0);
+        uint8_t kind = (dense_row ? 1 : 0) | (dense_alias_w ? 2 : 0);
         c->h_wkind[w] = kind;
         c->h_sp_off[w] = (uint32_t)list_total;
         c->h_hs_off[w] = (uint32_t)hash_total;
@@ -201,7 +201,13 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
             while (kMixClassCap[cl] >= 0 && cap > (kMixClassCap[cl] ? kMixClassCap[cl] : lds_max)) ++cl;
             mixc[cl].push_back(w);
             if (dense_row) {
-                if (!list_from_rebuild(c, w)) compact.push_back(w);
+                if (!list_from_rebuild(c, w)) {
+                    compact.push_back(w);
+                } else if (K <= kMixRowTopics && cw >= kMixRowMinTokens) {
+                    kind |= (uint8_t)kKindListOnly;  // served from its list everywhere
+                    c->h_wkind[w] = kind;
+                    list_only.push_back(w);
+                }
             } else {
                 sparse.push_back(w);
                 uint32_t hcap = 2;
@@ -221,6 +227,8 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
     c->total_hash = (int64_t)hash_total;
     c->n_dense_alias = (int32_t)dense_alias.size();
     c->n_mix = (int32_t)mix.size();
+    c->n_list_only = (int32_t)list_only.size();
+    sparse.insert(sparse.end(), list_only.begin(), list_only.end());  // d_sparse_words: see common.hpp
     c->n_sparse = (int32_t)sparse.size();
     c->n_compact = (int32_t)compact.size();
     if (c->n_dense_alias > 0 && K > lds_max && (double)H * (double)K > 4.0e9)
@@ -455,6 +463,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     c->zt_mask = c->zt_pack16 ? 0xFFFFu : 0xFFFFFFFFu;
     TRY(dev_alloc(c, &c->d_woff, (size_t)V + 1, "word offsets"));
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
+    // rows of list-only words (kKindListOnly) are never written: all zero from here on
+    if (hybrid) TRY_HIP(hipMemsetAsync(c->d_nkw, 0, sizeof(int32_t) * VK, c->stream));
     TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));
     TRY(dev_alloc(c, &c->d_cap, (size_t)V, "alias capacities"));
     TRY(dev_alloc(c, &c->d_chunk_doc, chunk_doc.size(), "document tiles"));
@@ -511,7 +521,8 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     for (int32_t w = 0; w < H; ++w) {
         const int32_t b = woff[w], e = woff[w + 1];
         if (e - b <= tile_tokens) {
-            tiles.push_back(RebuildTile{w, b, e, list_from_rebuild(c, w) ? 2 : 0});
+            const int32_t form = !list_from_rebuild(c, w) ? 0 : ((c->h_wkind[w] & kKindListOnly) ? 3 : 2);
+            tiles.push_back(RebuildTile{w, b, e, form});
         } else {
             multi.push_back(w);
             for (int32_t p = b; p < e; p += tile_tokens)
@@ -661,7 +672,7 @@ int lda_get_nkw_row(lda_ctx* c, int32_t w, int32_t* row)
     if (!c) return LDA_ERR_ARG;
     if (!row || w < 0 || w >= c->V) return fail(c, LDA_ERR_ARG, "lda_get_nkw_row: bad argument");
     if (c->state == SWEPT) return fail(c, LDA_ERR_STATE, "lda_get_nkw_row: counts are stale");
-    if (c->hybrid && !(c->h_wkind[w] & 1)) {  // sparse row: densify its list
+    if (c->hybrid && (!(c->h_wkind[w] & 1) || (c->h_wkind[w] & kKindListOnly))) {  // densify its list
         int32_t nnz = 0;
         LDA_HIP(c, hipMemcpyAsync(&nnz, c->d_sp_nnz + w, sizeof(int32_t), hipMemcpyDeviceToHost,
                                   c->stream));

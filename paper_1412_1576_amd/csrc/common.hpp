@@ -30,7 +30,8 @@ struct RebuildTile {
     int32_t p0;
     int32_t p1;
     int32_t multi;  // 1: the word has several tiles (row pre-zeroed, merged by atomics);
-                    // 2: single tile of a mixture word, whose list of non-zeros is written too
+                    // 2: single tile of a mixture word, whose list of non-zeros is written too;
+                    // 3: single tile of a list-only word (kKindListOnly): the list, not the row
 };
 
 }  // namespace lda
@@ -127,8 +128,10 @@ struct lda_ctx {
     // workspace)
     int32_t* d_mix_class[lda::kMixClasses] = {};
     int32_t n_mix_class[lda::kMixClasses] = {};
-    int32_t* d_sparse_words = nullptr;   // words with a sparse row (subset of the mixture words)
+    int32_t* d_sparse_words = nullptr;   // words whose n_kw row lives as a list: sparse rows and
+                                         // list-only words (the log-likelihood sums over these lists)
     int32_t n_sparse = 0;
+    int32_t n_list_only = 0;             // words marked kKindListOnly
     int32_t* d_compact_words = nullptr;  // mixture words with a dense row (list made by compaction)
     int32_t n_compact = 0;
     uint32_t* d_sp_off = nullptr;        // [V+1] first list entry of word w (capacity min(c_w, K))
@@ -153,7 +156,9 @@ struct lda_ctx {
     bool side_pending = false;           // side_join recorded, not yet waited for
     int64_t total_list = 0, total_hash = 0;
     std::vector<int32_t> h_wcount;       // corpus frequency of every word
-    std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table
+    std::vector<uint8_t> h_wkind;        // bit 0: dense row, bit 1: dense proposal table,
+                                         // bit 2 (kKindListOnly): the dense row is allotted but
+                                         // not kept -- see kKindListOnly
     std::vector<uint32_t> h_sp_off, h_hs_off;
     // scratch
     // sparse rows by one global sort (layout.hip): word index of every sparse-row token, keys,
@@ -242,6 +247,18 @@ __host__ __device__ inline uint4 pack_mix_bin(uint32_t split, int32_t t_own, int
                       (uint32_t)t_other | ((uint32_t)n_other << kMixTopicBits),
                       ((uint32_t)n_own >> 12) | (((uint32_t)n_other >> 12) << 16));
 }
+// A mixture word with a dense row, at least kMixRowMinTokens tokens, K <= kMixRowTopics and a
+// segment that fits one rebuild tile is served everywhere from its list of non-zeros: the
+// word pass rebuilds its row in LDS from the list, the table build reads the list, the
+// log-likelihood sums over it.  Rewriting its K-entry dense row at every count rebuild would
+// be the largest write of the rebuild (c3: 5.4 of 6.4 GB) for nobody to read, so the row is
+// left untouched (all zero since lda_init) and the word is marked with this bit; the rare
+// lookup outside the word pass (fused sweep) searches the word's mixture table, whose bins
+// are its non-zero topics in ascending order.
+constexpr uint32_t kKindListOnly = 4u;
+constexpr int32_t kMixRowTopics = 16384;   // largest K whose n_kw row a mixture item keeps in LDS
+constexpr int32_t kMixRowMinTokens = 128;
+
 __host__ __device__ inline void unpack_mix_bin(const uint4& e, bool own, int32_t& topic,
                                                int32_t& count)
 {

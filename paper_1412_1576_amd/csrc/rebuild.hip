@@ -97,7 +97,7 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
             const int32_t v = hist[k];
             if (v) atomicAdd(&row[k], v);
         }
-    } else if (t.multi == 2) {
+    } else if (t.multi >= 2) {
         // the whole row is here (one tile, one topic range): write it and the list of its
         // non-zero topics, ascending
         const size_t off = sp_off[t.w];
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
         for (int32_t kb = kb0; kb < kb1; kb += 64) {
             const int32_t k = kb + lane;
             const int32_t v = (k < kb1) ? hist[k] : 0;
-            if (k < kb1) row[k] = v;
+            if (k < kb1 && t.multi == 2) row[k] = v;  // 3: the row is not kept
             cnt += (uint32_t)__popcll(__ballot(v > 0));
         }
         if (lane == 0) wcnt[wv] = cnt;

@@ -36,8 +36,6 @@ namespace {
 
 constexpr int32_t kRowItemTokens = 32768;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
-constexpr int32_t kMixRowTopics = 16384;   // largest K whose n_kw row a mixture item keeps in LDS
-constexpr int32_t kMixRowMinTokens = 128;
 constexpr int32_t kPieceTokens = 4096;     // tokens of a gather piece
 constexpr int32_t kPieceWords = 4096;      // words of a gather piece (their offsets sit in LDS)
 
@@ -960,7 +958,7 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
     const bool rows_fit = c->K <= max_alias_topics();
     for (int32_t w = 0; w < V; ++w) {
         const int32_t b = woff[w], n = woff[w + 1] - b;
-        const bool dense_dense = !c->hybrid || c->h_wkind[w] == 3;
+        const bool dense_dense = !c->hybrid || (c->h_wkind[w] & 3) == 3;
         if (n >= kRowMinTokens && rows_fit && dense_dense) {
             close_piece(w);
             for (int32_t p = b; p < b + n; p += kRowItemTokens)
@@ -969,7 +967,7 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff)
         }
         // a mixture word with a dense row of at most kMixRowTopics topics and enough
         // tokens to pay for clearing an LDS row
-        if (c->hybrid && c->h_wkind[w] == 1 && c->K <= kMixRowTopics && n >= kMixRowMinTokens) {
+        if (c->hybrid && (c->h_wkind[w] & 3) == 1 && c->K <= kMixRowTopics && n >= kMixRowMinTokens) {
             close_piece(w);
             for (int32_t p = b; p < b + n; p += kRowItemTokens)
                 mix_items.push_back(make_int4(w, p, std::min(kRowItemTokens, b + n - p), 0));

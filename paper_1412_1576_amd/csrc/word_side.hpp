@@ -16,7 +16,8 @@ struct WordSide {
     const uint4* tab;  // the word's own table: K dense bins, or its mixture bins
     const void* row;   // dense n_kw row (int32[K]), or hash row (uint2[2^lg]) in store 2
     uint32_t n, C;     // bins and capacity of the own table
-    uint32_t kind;     // bit 0: dense n_kw row, bit 1: dense proposal table
+    uint32_t kind;     // bit 0: dense n_kw row, bit 1: dense proposal table, bit 2: the row is
+                       // not kept (kKindListOnly): lookups search the word's mixture table
     uint32_t lg;
     uint64_t QS;       // integer mass of the sparse term (mixture form)
 };
@@ -41,10 +42,28 @@ __device__ __forceinline__ WordSide load_word(const Args& A, int32_t w)
     return v;
 }
 
+// n_kw[w][t] of a list-only word: bin i of its mixture table carries its i-th non-zero topic
+// (ascending) and that topic's count
+__device__ __forceinline__ int32_t nkw_from_table(const WordSide& v, int32_t t)
+{
+    uint32_t lo = 0, hi = v.n;  // first bin whose topic is >= t
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        int32_t topic, count;
+        unpack_mix_bin(v.tab[mid], true, topic, count);
+        if (topic < t) lo = mid + 1; else hi = mid;
+    }
+    if (lo == v.n) return 0;
+    int32_t topic, count;
+    unpack_mix_bin(v.tab[lo], true, topic, count);
+    return topic == t ? count : 0;
+}
+
 // n_kw[w][t]: dense row, or the word's hash row (Sec. 5)
 template <int STORE>
 __device__ __forceinline__ int32_t nkw_lookup(const WordSide& v, int32_t t)
 {
+    if (v.kind & kKindListOnly) return nkw_from_table(v, t);
     if (STORE != 2 || (v.kind & 1u)) return static_cast<const int32_t*>(v.row)[t];
     const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
     const uint32_t mask = (1u << v.lg) - 1u;
@@ -70,7 +89,10 @@ template <int STORE>
 __device__ __forceinline__ NkwProbe nkw_probe_begin(const WordSide& v, int32_t t)
 {
     NkwProbe p;
-    if (STORE != 2 || (v.kind & 1u)) {
+    if (v.kind & kKindListOnly) {  // resolved here; nkw_probe_finish returns it
+        p.slot = 0;
+        p.e = make_uint2((uint32_t)nkw_from_table(v, t), 0u);
+    } else if (STORE != 2 || (v.kind & 1u)) {
         p.slot = 0;
         p.e = make_uint2((uint32_t) static_cast<const int32_t*>(v.row)[t], 0u);
     } else {
@@ -83,7 +105,7 @@ __device__ __forceinline__ NkwProbe nkw_probe_begin(const WordSide& v, int32_t t
 template <int STORE>
 __device__ __forceinline__ int32_t nkw_probe_finish(const WordSide& v, int32_t t, const NkwProbe& p)
 {
-    if (STORE != 2 || (v.kind & 1u)) return (int32_t)p.e.x;
+    if (STORE != 2 || (v.kind & (1u | kKindListOnly))) return (int32_t)p.e.x;
     if (p.e.x == (uint32_t)t) return (int32_t)p.e.y;
     if (p.e.x == 0xFFFFFFFFu) return 0;
     const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
