@@ -281,6 +281,14 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
     b_run = b_wave;
     uint32_t b_prev = 0;  // partner of the last light met so far
     uint32_t a_prev = 0;  // partner of the last heavy met so far
+    // Lists in global memory: every probe of a search is a round trip to L2, and a round's
+    // searches are a chain of them.  The 64 list entries that follow the previous round's
+    // result are therefore read once, by the whole wave, and kept in a window in LDS; when
+    // the round's last partner lies inside the window (the usual case) every lane's own
+    // search runs on the window.
+    __shared__ uint64_t s_win[GLOBAL ? kMaxWaves * 2 * kWave : 1];
+    uint64_t* const xwin = s_win + (GLOBAL ? wv * 2 * kWave : 0);  // X of heavies b_prev + i
+    uint64_t* const dwin = xwin + (GLOBAL ? kWave : 0);            // Delta of lights a_prev + i
     typename Sink::Loaded pend_v{};
     int32_t pend_k = -1;
     uint32_t pend_split = 0, pend_al = 0;
@@ -299,24 +307,57 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
         if (light) own = M::ld(&dx[a_run + la]);
         if (heavy) own = M::ld(&dx[n - b_own]);
         uint32_t b_hi = b_prev, a_hi = a_prev;
+        bool xwin_ok = false, dwin_ok = false;  // uniform: the round's partners are in the window
         if (lmask != 0) {  // uniform
             const uint64_t delta_last = readlane_u64(own, 63 - __clzll((unsigned long long)lmask));
             // first b with X_b > delta; X_{B-1} = total deficit > every delta
-            b_hi = wave_first_true(b_prev, B - 1, lane,
-                                   [&](uint32_t i) { return M::ld(&dx[n - i]) > delta_last; });
+            uint32_t from = b_prev;
+            if constexpr (GLOBAL) {
+                const uint32_t top = (B - 1 - b_prev > 63u) ? b_prev + 63u : B - 1;
+                const uint32_t idx = (b_prev + (uint32_t)lane < top) ? b_prev + (uint32_t)lane : top;
+                const uint64_t xv = M::ld(&dx[n - idx]);
+                const uint64_t hit = __ballot(xv > delta_last);
+                if (hit != 0) {
+                    b_hi = b_prev + (uint32_t)(__ffsll((unsigned long long)hit) - 1);
+                    xwin[lane] = xv;
+                    xwin_ok = true;
+                } else {
+                    from = top + 1;  // top < B - 1 here, because X_{B-1} > delta
+                }
+            }
+            if (!xwin_ok)
+                b_hi = wave_first_true(from, B - 1, lane,
+                                       [&](uint32_t i) { return M::ld(&dx[n - i]) > delta_last; });
         }
         if (hmask != 0) {  // uniform
             const uint64_t x_last = readlane_u64(own, 63 - __clzll((unsigned long long)hmask));
             // first a with Delta_a >= X; Delta_A = total excess >= every X
-            a_hi = wave_first_true(a_prev, A, lane,
-                                   [&](uint32_t i) { return M::ld(&dx[i]) >= x_last; });
+            uint32_t from = a_prev;
+            if constexpr (GLOBAL) {
+                const uint32_t top = (A - a_prev > 63u) ? a_prev + 63u : A;
+                const uint32_t idx = (a_prev + (uint32_t)lane < top) ? a_prev + (uint32_t)lane : top;
+                const uint64_t dv = M::ld(&dx[idx]);
+                const uint64_t hit = __ballot(dv >= x_last);
+                if (hit != 0) {
+                    a_hi = a_prev + (uint32_t)(__ffsll((unsigned long long)hit) - 1);
+                    dwin[lane] = dv;
+                    dwin_ok = true;
+                } else {
+                    from = top + 1;  // top < A here, because Delta_A >= X
+                }
+            }
+            if (!dwin_ok)
+                a_hi = wave_first_true(from, A, lane,
+                                       [&](uint32_t i) { return M::ld(&dx[i]) >= x_last; });
         }
+        if constexpr (GLOBAL) __builtin_amdgcn_wave_barrier();  // windows written before they are read
         uint32_t split = 0, al = 0;
         if (light) {
             uint32_t lo = b_prev, hi = b_hi;
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (M::ld(&dx[n - mid]) > own) hi = mid; else lo = mid + 1;
+                const uint64_t x = (GLOBAL && xwin_ok) ? xwin[mid - b_prev] : M::ld(&dx[n - mid]);
+                if (x > own) hi = mid; else lo = mid + 1;
             }
             split = (uint32_t)m;
             al = M::ld(&hidx[lo]);
@@ -324,9 +365,10 @@ __device__ __forceinline__ void build_alias_table(int32_t n, const Src& src, con
             uint32_t lo = a_prev, hi = a_hi;
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (M::ld(&dx[mid]) >= own) hi = mid; else lo = mid + 1;
+                const uint64_t d = (GLOBAL && dwin_ok) ? dwin[mid - a_prev] : M::ld(&dx[mid]);
+                if (d >= own) hi = mid; else lo = mid + 1;
             }
-            const uint64_t sp = C + own - M::ld(&dx[lo]);
+            const uint64_t sp = C + own - ((GLOBAL && dwin_ok) ? dwin[lo - a_prev] : M::ld(&dx[lo]));
             split = (uint32_t)sp;
             al = (sp < C) ? M::ld(&hidx[b_own + 1]) : (uint32_t)k;
         }
