@@ -9,7 +9,7 @@
 //
 //   word pass  word-major.  Frequent words: a workgroup stages the word's n_kw row and
 //              its table in LDS and serves a run of the word's tokens from there
-//              (one coalesced read of the rows per 32768 tokens instead of three random
+//              (one coalesced read of the rows per 65536 tokens instead of three random
 //              128-byte lines per token).  Short words: the rows are gathered; the
 //              word's tokens are processed together, so its lines are reused in L2.
 //              Output: one record per token (n_kw at its snapshot topic, the proposed
@@ -34,7 +34,7 @@ namespace lda {
 
 namespace {
 
-constexpr int32_t kRowItemTokens = 32768;  // tokens a workgroup serves from one staging of the rows
+constexpr int32_t kRowItemTokens = 65536;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
 constexpr int32_t kPieceTokens = 4096;     // tokens of a gather piece
 constexpr int32_t kPieceWords = 4096;      // words of a gather piece (their offsets sit in LDS)
