@@ -30,6 +30,9 @@
  *     throws.  lda_last_error() returns a message for the last failure.
  *   - lda_build_alias, lda_sweep and lda_rebuild_counts enqueue work on the
  *     context's HIP stream and return; accessors and lda_loglik synchronise.
+ *     (lda_build_alias may run part of its kernels on a second stream of the
+ *     library's own, of default priority, forked from and joined to the context's
+ *     stream by events: work queued after the call still sees every table.)
  *   - A context is not thread-safe.  Calls must follow the state machine
  *       COUNTS_VALID --lda_build_alias--> ALIAS_VALID --lda_sweep--> SWEPT
  *       SWEPT --lda_rebuild_counts--> COUNTS_VALID
