@@ -97,7 +97,7 @@ typedef struct lda_options {
  *   D            number of documents (>= 1); empty documents are legal
  *   V, K         vocabulary size and number of topics (>= 1); K <= 2^20 - 2; dense rows and
  *                dense tables are limited to 10^10 and 4 * 10^9 entries (LDA_ERR_UNSUPPORTED)
- *   doc_offsets  [D+1] host, doc_offsets[0] = 0, non-decreasing, N = doc_offsets[D] in [1, 2^31-2]
+ *   doc_offsets  [D+1] host, doc_offsets[0] = 0, non-decreasing, N = doc_offsets[D] in [1, 2^31 - 2^20 - 1]
  *   word_ids     [N] host, each in [0, V)
  *   alpha, beta  symmetric Dirichlet parameters (> 0) of Eq. (1)
  *   seed         Philox key

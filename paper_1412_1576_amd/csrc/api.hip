@@ -334,7 +334,10 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
             return fail(nullptr, LDA_ERR_ARG, "lda_init: doc_offsets decreases at %lld", (long long)d);
     const int64_t N = doc_offsets[D];
     if (N < 1) return fail(nullptr, LDA_ERR_ARG, "lda_init: empty corpus");
-    if (N > 2147483646LL) return fail(nullptr, LDA_ERR_ARG, "lda_init: N must be < 2^31 - 1");
+    // token positions are 32-bit; kernels look up to a few thousand positions past a segment's end
+    // in their loop conditions, so the margin keeps every such sum representable
+    if (N > 2147483647LL - (1LL << 20))
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: N must be at most 2^31 - 2^20 - 1 tokens");
     lda_options o{};
     if (opt) o = *opt;
     if (o.proposal_mode < 0 || o.proposal_mode > 2)

@@ -176,3 +176,33 @@ def test_c4_full_size_properties(lda_mod):
 def test_c5_full_size_properties(lda_mod):
     cfg = corpus.CONFIGS["c5"]
     property_check(lda_mod, cfg, -1, cfg.mh_steps)
+
+
+@pytest.mark.timeout(900)
+def test_near_the_token_limit(lda_mod):
+    """2.11 * 10^9 tokens (the limit is 2^31 - 2^20 - 1): token positions are 32-bit, so this
+    is where an overflow in the index arithmetic would show.  No oracle at this size: counts
+    and sampled rows against numpy recounts of the library's own z."""
+    cfg = corpus.scaled(corpus.CONFIGS["c3"], D=23_500_000, K=1000, alpha=0.05)
+    doff, words = corpus.make_corpus(cfg)
+    N = int(doff[-1])
+    assert 2_100_000_000 < N <= 2**31 - 2**20 - 1
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=1, dense_rows=0,
+                    dense_alias_min_count=cfg.K)
+    assert g.N == N
+    ll0 = g.loglik()[0]
+    for _ in range(2):
+        g.build_alias()
+        g.sweep(2)
+        g.rebuild_counts()
+    nk = g.get_nk()
+    z = g.get_z()
+    assert 0 <= z.min() and z.max() < cfg.K
+    assert np.array_equal(np.bincount(z, minlength=cfg.K), nk)
+    for d in (0, 1, cfg.D // 2, cfg.D - 1):
+        assert np.array_equal(g.get_ndk_row(d),
+                              np.bincount(z[doff[d]:doff[d + 1]], minlength=cfg.K)), d
+    for w in (0, 5, 1000, cfg.V - 1):  # a dense-table word, mixture words, the rarest word
+        assert np.array_equal(g.get_nkw_row(w), np.bincount(z[words == w], minlength=cfg.K)), w
+    assert g.loglik()[0] > ll0
+    g.close()
