@@ -53,7 +53,7 @@ def doc_pass_bytes_per_token(mh_steps: int) -> float:
 # fetched + written); keyed by (workload, mh_steps, dense_alias_min_count).  None where not
 # measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2, 10000): (17_722_963.7 * 2.000 + 12_913_489.0 * 1.000) * 1024.0,
+    ("c3", 2, 10000): (17_724_965.2 * 2.000 + 12_911_892.6 * 1.000) * 1024.0,
 }
 
 
