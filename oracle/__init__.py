@@ -53,6 +53,9 @@ def bind(path):
         "ldaref_mh_accept": (C.c_int, [C.c_int] + [C.c_int32] * 9 + [C.c_double] * 3 + [C.c_uint32]),
         "ldaref_init": (C.c_int, [C.POINTER(vp), C.c_int64, C.c_int32, C.c_int32, _i64p, _i32p,
                                   C.c_double, C.c_double, C.c_uint64, C.c_int32, C.c_int32]),
+        "ldaref_init_ex": (C.c_int, [C.POINTER(vp), C.c_int64, C.c_int32, C.c_int32, _i64p, _i32p,
+                                     C.c_double, C.c_double, C.c_uint64, C.c_int32, C.c_int32,
+                                     C.c_int32]),
         "ldaref_destroy": (None, [vp]),
         "ldaref_set_lazy_alias": (None, [vp, C.c_int32]),
         "ldaref_build_alias": (C.c_int, [vp]),
@@ -150,15 +153,18 @@ class Oracle:
     """Host-memory LDA state with the same call sequence as the GPU library."""
 
     def __init__(self, doc_offsets, word_ids, V, K, alpha, beta, seed=0,
-                 dense_alias_min_count=0, proposal_mode=0, lazy_alias=False):
+                 dense_alias_min_count=0, proposal_mode=0, lazy_alias=False, lazy_rows=False):
+        """lazy_alias: a word's table is built when a draw first needs it.  lazy_rows: a
+        word's n_kw row (and dense table) is allocated and counted when first needed, for
+        vocabularies whose V x K table does not fit in memory.  Neither changes a result."""
         self._h = C.c_void_p()
         doc_offsets = np.ascontiguousarray(doc_offsets, np.int64)
         word_ids = np.ascontiguousarray(word_ids, np.int32)
         self.D = len(doc_offsets) - 1
         self.V, self.K = int(V), int(K)
-        _ck(lib().ldaref_init(C.byref(self._h), self.D, self.V, self.K, doc_offsets, word_ids,
-                              float(alpha), float(beta), int(seed), int(dense_alias_min_count),
-                              int(proposal_mode)), "ldaref_init")
+        _ck(lib().ldaref_init_ex(C.byref(self._h), self.D, self.V, self.K, doc_offsets, word_ids,
+                                 float(alpha), float(beta), int(seed), int(dense_alias_min_count),
+                                 int(proposal_mode), 1 if lazy_rows else 0), "ldaref_init")
         self.N = int(lib().ldaref_num_tokens(self._h))
         if lazy_alias:
             lib().ldaref_set_lazy_alias(self._h, 1)

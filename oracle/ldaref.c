@@ -38,7 +38,9 @@
  * closed-form (merge) equivalence; detailed balance of the coded acceptance
  * against Eq. (4) computed independently; exact m-step distribution vs chain
  * histogram; doc-draw histogram vs (n_dk+alpha); count invariants vs numpy
- * recount; log-likelihood vs scipy gammaln and a K=1 closed form.
+ * recount; log-likelihood vs scipy gammaln and a K=1 closed form.  The two storage
+ * options (tables built on first use, n_kw rows counted on first use) are pinned to the
+ * plain form bit for bit.
  */
 #include <math.h>
 #include <stdint.h>
@@ -280,12 +282,23 @@ typedef struct ldaref_ctx {
     int32_t* wcount;               /* [V] corpus frequency */
     int32_t* z;                    /* [N] snapshot */
     int32_t* znew;                 /* [N] */
-    int32_t* nkw;                  /* [V*K] */
+    /* n_kw: one row of K counts per word, reached through nkw_row[w].  Default: every row
+     * lives in one V*K block and is counted by count_all.  With lazy_rows (vocabularies
+     * whose V*K table does not fit in memory) a row is allocated and counted from the
+     * word's tokens when it is first asked for and dropped when the counts go stale; the
+     * numbers in a row are the same either way. */
+    int32_t** nkw_row;             /* [V]; NULL = not counted yet (lazy_rows only) */
+    int32_t* nkw_block;            /* [V*K] backing store of all rows (not lazy_rows) */
+    int32_t lazy_rows;
+    int64_t* wtok_off;             /* [V+1] lazy_rows: tokens of word w are            */
+    int32_t* wtok;                 /* [N]   wtok[wtok_off[w] .. wtok_off[w+1]), ascending */
     int32_t* nk;                   /* [K] */
     int32_t* doc_scratch;          /* [K] dense n_dk row of the current document */
     /* word-proposal tables */
-    uint32_t* split;               /* [V*K] dense form */
-    uint32_t* alias;               /* [V*K] */
+    uint32_t** split_row;          /* [V] dense form: K bins of word w (lazy_rows: NULL until built) */
+    uint32_t** alias_row;          /* [V] */
+    uint32_t* split_block;         /* [V*K] backing store (not lazy_rows) */
+    uint32_t* alias_block;
     uint32_t* cap;                 /* [V] */
     uint8_t* built;                /* [V] table valid for the current snapshot */
     sparse_table* sparse;          /* [V] mixture form: per-word sparse term */
@@ -315,26 +328,57 @@ void ldaref_destroy(ldaref_ctx* c)
     if (c->sparse)
         for (int32_t w = 0; w < c->V; ++w) free_sparse(&c->sparse[w]);
     free(c->sparse); free(c->bsplit); free(c->balias);
+    if (c->lazy_rows) {
+        for (int32_t w = 0; w < c->V; ++w) {
+            if (c->nkw_row) free(c->nkw_row[w]);
+            if (c->split_row) free(c->split_row[w]);
+            if (c->alias_row) free(c->alias_row[w]);
+        }
+    }
+    free(c->nkw_row); free(c->nkw_block); free(c->wtok_off); free(c->wtok);
+    free(c->split_row); free(c->alias_row); free(c->split_block); free(c->alias_block);
     free(c->doff); free(c->word); free(c->wcount); free(c->z); free(c->znew);
-    free(c->nkw); free(c->nk); free(c->doc_scratch);
-    free(c->split); free(c->alias); free(c->cap); free(c->built);
+    free(c->nk); free(c->doc_scratch);
+    free(c->cap); free(c->built);
     free(c);
 }
 
 static void count_all(ldaref_ctx* c)
 {
-    memset(c->nkw, 0, sizeof(int32_t) * (size_t)c->V * (size_t)c->K);
     memset(c->nk, 0, sizeof(int32_t) * (size_t)c->K);
+    if (c->lazy_rows) {
+        /* rows counted from an older assignment are dropped; nkw_row_of recounts on demand */
+        for (int32_t w = 0; w < c->V; ++w) {
+            free(c->nkw_row[w]);
+            c->nkw_row[w] = NULL;
+        }
+    } else {
+        memset(c->nkw_block, 0, sizeof(int32_t) * (size_t)c->V * (size_t)c->K);
+    }
     for (int64_t g = 0; g < c->N; ++g) {
-        c->nkw[(size_t)c->word[g] * (size_t)c->K + (size_t)c->z[g]] += 1;
+        if (!c->lazy_rows) c->nkw_row[c->word[g]][c->z[g]] += 1;
         c->nk[c->z[g]] += 1;
     }
     /* n_dk rows are formed per document from z when needed (doc_scratch) */
 }
 
-int ldaref_init(ldaref_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_offsets,
-                const int32_t* word_ids, double alpha, double beta, uint64_t seed,
-                int32_t dense_alias_min_count, int32_t proposal_mode)
+/* Row w of n_kw for the current assignment; NULL: out of memory (lazy_rows only). */
+static const int32_t* nkw_row_of(ldaref_ctx* c, int32_t w)
+{
+    if (!c->nkw_row[w]) {
+        int32_t* row = (int32_t*)calloc((size_t)c->K, sizeof(int32_t));
+        if (!row) return NULL;
+        for (int64_t i = c->wtok_off[w]; i < c->wtok_off[w + 1]; ++i) row[c->z[c->wtok[i]]] += 1;
+        c->nkw_row[w] = row;
+    }
+    return c->nkw_row[w];
+}
+
+/* lazy_rows != 0: n_kw rows and dense tables are allocated per word on first use (see the
+ * context); everything the oracle computes is the same. */
+int ldaref_init_ex(ldaref_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_offsets,
+                   const int32_t* word_ids, double alpha, double beta, uint64_t seed,
+                   int32_t dense_alias_min_count, int32_t proposal_mode, int32_t lazy_rows)
 {
     if (!out || !doc_offsets || D < 1 || V < 1 || K < 1 || !(alpha > 0.0) || !(beta > 0.0))
         return LDAREF_ERR_ARG;
@@ -356,31 +400,57 @@ int ldaref_init(ldaref_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t
     c->seed = seed;
     c->dense_alias_min_count = dense_alias_min_count;
     c->proposal_mode = proposal_mode;
+    c->lazy_rows = lazy_rows ? 1 : 0;
     const size_t VK = (size_t)V * (size_t)K;
     c->doff = (int64_t*)malloc(sizeof(int64_t) * (size_t)(D + 1));
     c->word = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
     c->wcount = (int32_t*)calloc((size_t)V, sizeof(int32_t));
     c->z = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
     c->znew = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
-    c->nkw = (int32_t*)calloc(VK, sizeof(int32_t));
+    c->nkw_row = (int32_t**)calloc((size_t)V, sizeof(int32_t*));
+    c->split_row = (uint32_t**)calloc((size_t)V, sizeof(uint32_t*));
+    c->alias_row = (uint32_t**)calloc((size_t)V, sizeof(uint32_t*));
+    if (c->lazy_rows) {
+        c->wtok_off = (int64_t*)calloc((size_t)V + 1, sizeof(int64_t));
+        c->wtok = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+    } else {
+        c->nkw_block = (int32_t*)calloc(VK, sizeof(int32_t));
+        c->split_block = (uint32_t*)calloc(VK, sizeof(uint32_t));
+        c->alias_block = (uint32_t*)calloc(VK, sizeof(uint32_t));
+    }
     c->nk = (int32_t*)calloc((size_t)K, sizeof(int32_t));
     c->doc_scratch = (int32_t*)calloc((size_t)K, sizeof(int32_t));
-    c->split = (uint32_t*)calloc(VK, sizeof(uint32_t));
-    c->alias = (uint32_t*)calloc(VK, sizeof(uint32_t));
     c->cap = (uint32_t*)calloc((size_t)V, sizeof(uint32_t));
     c->built = (uint8_t*)calloc((size_t)V, 1);
     c->sparse = (sparse_table*)calloc((size_t)V, sizeof(sparse_table));
     c->bsplit = (uint32_t*)calloc((size_t)K, sizeof(uint32_t));
     c->balias = (uint32_t*)calloc((size_t)K, sizeof(uint32_t));
-    if (!c->doff || !c->word || !c->wcount || !c->z || !c->znew || !c->nkw || !c->nk ||
-        !c->doc_scratch || !c->split || !c->alias || !c->cap || !c->built || !c->sparse ||
-        !c->bsplit || !c->balias) {
+    const int rows_ok = c->lazy_rows ? (c->wtok_off && c->wtok)
+                                     : (c->nkw_block && c->split_block && c->alias_block);
+    if (!c->doff || !c->word || !c->wcount || !c->z || !c->znew || !c->nkw_row || !c->nk ||
+        !c->doc_scratch || !c->split_row || !c->alias_row || !rows_ok || !c->cap || !c->built ||
+        !c->sparse || !c->bsplit || !c->balias) {
         ldaref_destroy(c);
         return LDAREF_ERR_OOM;
     }
     memcpy(c->doff, doc_offsets, sizeof(int64_t) * (size_t)(D + 1));
     memcpy(c->word, word_ids, sizeof(int32_t) * (size_t)N);
     for (int64_t g = 0; g < N; ++g) c->wcount[c->word[g]] += 1;
+    if (c->lazy_rows) {
+        /* the tokens of every word, in ascending token order (counting sort) */
+        for (int32_t w = 0; w < V; ++w) c->wtok_off[w + 1] = c->wtok_off[w] + c->wcount[w];
+        int64_t* next = (int64_t*)malloc(sizeof(int64_t) * (size_t)V);
+        if (!next) { ldaref_destroy(c); return LDAREF_ERR_OOM; }
+        memcpy(next, c->wtok_off, sizeof(int64_t) * (size_t)V);
+        for (int64_t g = 0; g < N; ++g) c->wtok[next[c->word[g]]++] = (int32_t)g;
+        free(next);
+    } else {
+        for (int32_t w = 0; w < V; ++w) {
+            c->nkw_row[w] = c->nkw_block + (size_t)w * (size_t)K;
+            c->split_row[w] = c->split_block + (size_t)w * (size_t)K;
+            c->alias_row[w] = c->alias_block + (size_t)w * (size_t)K;
+        }
+    }
     /* initial assignment: uniform topic from the token's own Philox stream,
        counter (g, 0xFFFFFFFF, 0) */
     for (int64_t g = 0; g < N; ++g) {
@@ -395,6 +465,16 @@ int ldaref_init(ldaref_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t
     return LDAREF_OK;
 }
 
+int ldaref_init(ldaref_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_offsets,
+                const int32_t* word_ids, double alpha, double beta, uint64_t seed,
+                int32_t dense_alias_min_count, int32_t proposal_mode)
+{
+    return ldaref_init_ex(out, D, V, K, doc_offsets, word_ids, alpha, beta, seed,
+                          dense_alias_min_count, proposal_mode, 0);
+}
+
+/* lazy != 0: ldaref_build_alias builds only the shared table; a word's table is built from
+ * the same counts when a draw first needs it.  The tables are the same either way. */
 void ldaref_set_lazy_alias(ldaref_ctx* c, int32_t lazy) { c->lazy_alias = lazy ? 1 : 0; }
 
 /* Mixture form (Sec. 4.2): p_w = n_kw/(n_k+betabar) [sparse, per word]
@@ -418,12 +498,15 @@ static int build_beta_table(ldaref_ctx* c)
 static int build_word_table(ldaref_ctx* c, int32_t w)
 {
     const int32_t K = c->K;
-    const int32_t* row = c->nkw + (size_t)w * (size_t)K;
+    const int32_t* row = nkw_row_of(c, w);
+    if (!row) return LDAREF_ERR_OOM;
     int rc = LDAREF_OK;
     if (word_is_dense(c, w)) {
-        rc = ldaref_alias_build_dense_row(K, row, c->nk, c->beta, c->betabar,
-                                          c->split + (size_t)w * K, c->alias + (size_t)w * K,
-                                          &c->cap[w]);
+        if (!c->split_row[w]) c->split_row[w] = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)K);
+        if (!c->alias_row[w]) c->alias_row[w] = (uint32_t*)malloc(sizeof(uint32_t) * (size_t)K);
+        if (!c->split_row[w] || !c->alias_row[w]) return LDAREF_ERR_OOM;
+        rc = ldaref_alias_build_dense_row(K, row, c->nk, c->beta, c->betabar, c->split_row[w],
+                                          c->alias_row[w], &c->cap[w]);
     } else {
         sparse_table* s = &c->sparse[w];
         free_sparse(s);
@@ -450,7 +533,7 @@ static int build_word_table(ldaref_ctx* c, int32_t w)
             free(q0);
         }
     }
-    c->built[w] = 1;
+    if (rc == LDAREF_OK) c->built[w] = 1;
     return rc;
 }
 
@@ -474,46 +557,59 @@ int ldaref_build_alias(ldaref_ctx* c)
     return LDAREF_OK;
 }
 
-/* word-proposal draw for word w from (x0, x1, x3) */
-static int32_t word_draw(ldaref_ctx* c, int32_t w, uint32_t x0, uint32_t x1, uint32_t x3)
+/* word-proposal draw for word w from (x0, x1, x3) into *t */
+static int word_draw(ldaref_ctx* c, int32_t w, uint32_t x0, uint32_t x1, uint32_t x3, int32_t* t)
 {
     const int32_t K = c->K;
-    if (!c->built[w]) build_word_table(c, w);
+    if (!c->built[w]) {
+        int rc = build_word_table(c, w);
+        if (rc) return rc;
+    }
     if (word_is_dense(c, w)) {
-        return (int32_t)ldaref_alias_draw(K, c->split + (size_t)w * K, c->alias + (size_t)w * K,
-                                          c->cap[w], x0, x1);
+        *t = (int32_t)ldaref_alias_draw(K, c->split_row[w], c->alias_row[w], c->cap[w], x0, x1);
+        return LDAREF_OK;
     }
     const sparse_table* s = &c->sparse[w];
     double u3 = unit_open(x3);
     if (u3 * (double)(s->QS + c->QB) < (double)s->QS) {
         uint32_t i = ldaref_alias_draw(s->n, s->split, s->alias, s->C, x0, x1);
-        return s->topics[i];
+        *t = s->topics[i];
+        return LDAREF_OK;
     }
-    return (int32_t)ldaref_alias_draw(K, c->bsplit, c->balias, c->bC, x0, x1);
+    *t = (int32_t)ldaref_alias_draw(K, c->bsplit, c->balias, c->bC, x0, x1);
+    return LDAREF_OK;
 }
 
 /* One token's chain (Eq. 13): ndk = dense n_dk row of its document, zdoc = the
- * document's snapshot topics, L = document length. */
-static int32_t token_chain(ldaref_ctx* c, int64_t g, int32_t w, const int32_t* ndk,
-                           const int32_t* zdoc, int32_t L, uint32_t sweep, int32_t mh_steps)
+ * document's snapshot topics, L = document length.  The final topic goes to *out. */
+static int token_chain(ldaref_ctx* c, int64_t g, int32_t w, const int32_t* ndk,
+                       const int32_t* zdoc, int32_t L, uint32_t sweep, int32_t mh_steps,
+                       int32_t* out)
 {
     const int32_t K = c->K;
-    const int32_t* nkw = c->nkw + (size_t)w * (size_t)K;
+    const int32_t* nkw = nkw_row_of(c, w);
+    if (!nkw) return LDAREF_ERR_OOM;
     const int32_t z0 = c->z[g];
     int32_t s = z0;
     for (int32_t j = 0; j < mh_steps; ++j) {
         uint32_t x[4];
         token_random(c->seed, (uint64_t)g, sweep, (uint32_t)j, x);
         int word_step = (c->proposal_mode == 0) ? ((j & 1) == 0) : (c->proposal_mode == 1);
-        int32_t t = word_step ? word_draw(c, w, x[0], x[1], x[3])
-                              : ldaref_doc_draw(L, K, c->alphabar, zdoc, x[0], x[1]);
+        int32_t t;
+        if (word_step) {
+            int rc = word_draw(c, w, x[0], x[1], x[3], &t);
+            if (rc) return rc;
+        } else {
+            t = ldaref_doc_draw(L, K, c->alphabar, zdoc, x[0], x[1]);
+        }
         if (t != s) {
             if (ldaref_mh_accept(word_step, s, t, z0, ndk[s], ndk[t], nkw[s], nkw[t], c->nk[s],
                                  c->nk[t], c->alpha, c->beta, c->betabar, x[2]))
                 s = t;
         }
     }
-    return s;
+    *out = s;
+    return LDAREF_OK;
 }
 
 int ldaref_sweep(ldaref_ctx* c, int32_t mh_steps)
@@ -524,10 +620,13 @@ int ldaref_sweep(ldaref_ctx* c, int32_t mh_steps)
     for (int64_t d = 0; d < c->D; ++d) {
         const int64_t b = c->doff[d], e = c->doff[d + 1];
         const int32_t L = (int32_t)(e - b);
+        int rc = LDAREF_OK;
         for (int64_t g = b; g < e; ++g) ndk[c->z[g]] += 1;
-        for (int64_t g = b; g < e; ++g)
-            c->znew[g] = token_chain(c, g, c->word[g], ndk, c->z + b, L, c->sweep_index, mh_steps);
+        for (int64_t g = b; g < e && rc == LDAREF_OK; ++g)
+            rc = token_chain(c, g, c->word[g], ndk, c->z + b, L, c->sweep_index, mh_steps,
+                             &c->znew[g]);
         for (int64_t g = b; g < e; ++g) ndk[c->z[g]] = 0;
+        if (rc) return rc;
     }
     int32_t* tmp = c->z; c->z = c->znew; c->znew = tmp;
     c->sweep_index += 1;
@@ -555,9 +654,10 @@ int ldaref_sweep_tokens(ldaref_ctx* c, uint32_t sweep_index, int32_t mh_steps, i
         while (c->doff[lo + 1] <= g) ++lo;
         const int64_t b = c->doff[lo], e = c->doff[lo + 1];
         for (int64_t q = b; q < e; ++q) ndk[c->z[q]] += 1;
-        out[i] = token_chain(c, g, c->word[g], ndk, c->z + b, (int32_t)(e - b), sweep_index,
-                             mh_steps);
+        int rc = token_chain(c, g, c->word[g], ndk, c->z + b, (int32_t)(e - b), sweep_index,
+                             mh_steps, &out[i]);
         for (int64_t q = b; q < e; ++q) ndk[c->z[q]] = 0;
+        if (rc) return rc;
     }
     return LDAREF_OK;
 }
@@ -584,6 +684,12 @@ static void kadd(ksum* a, double x)
     a->s = t;
 }
 
+static int cmp_int32(const void* a, const void* b)
+{
+    const int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+    return (x > y) - (x < y);
+}
+
 int ldaref_loglik(ldaref_ctx* c, double* total, double* doc_part, double* word_part)
 {
     if (!c || !total) return LDAREF_ERR_ARG;
@@ -606,10 +712,31 @@ int ldaref_loglik(ldaref_ctx* c, double* total, double* doc_part, double* word_p
         }
     }
     for (int32_t k = 0; k < K; ++k) kadd(&sw, lgbb - lgamma((double)c->nk[k] + c->betabar));
-    for (int32_t w = 0; w < c->V; ++w) {
-        const int32_t* row = c->nkw + (size_t)w * (size_t)K;
-        for (int32_t k = 0; k < K; ++k)
-            if (row[k] > 0) kadd(&sw, lgamma((double)row[k] + c->beta) - lgb);
+    if (!c->lazy_rows) {
+        for (int32_t w = 0; w < c->V; ++w) {
+            const int32_t* row = c->nkw_row[w];
+            for (int32_t k = 0; k < K; ++k)
+                if (row[k] > 0) kadd(&sw, lgamma((double)row[k] + c->beta) - lgb);
+        }
+    } else {
+        /* the same terms in the same order (words ascending, topics ascending) without
+           K-entry rows: a word's distinct topics are collected from its tokens and sorted */
+        int32_t* cnt = (int32_t*)calloc((size_t)K, sizeof(int32_t));
+        int32_t* tl = (int32_t*)malloc(sizeof(int32_t) * (size_t)K);
+        if (!cnt || !tl) { free(cnt); free(tl); return LDAREF_ERR_OOM; }
+        for (int32_t w = 0; w < c->V; ++w) {
+            int32_t n = 0;
+            for (int64_t i = c->wtok_off[w]; i < c->wtok_off[w + 1]; ++i) {
+                const int32_t k = c->z[c->wtok[i]];
+                if (cnt[k]++ == 0) tl[n++] = k;
+            }
+            qsort(tl, (size_t)n, sizeof(int32_t), cmp_int32);
+            for (int32_t j = 0; j < n; ++j) {
+                kadd(&sw, lgamma((double)cnt[tl[j]] + c->beta) - lgb);
+                cnt[tl[j]] = 0;
+            }
+        }
+        free(cnt); free(tl);
     }
     const double dp = sd.s + sd.c, wp = sw.s + sw.c;
     if (doc_part) *doc_part = dp;
@@ -654,7 +781,9 @@ int ldaref_get_nkw_row(ldaref_ctx* c, int32_t w, int32_t* row)
 {
     if (!c || !row || w < 0 || w >= c->V) return LDAREF_ERR_ARG;
     if (c->state == ST_SWEPT) return LDAREF_ERR_STATE;
-    memcpy(row, c->nkw + (size_t)w * (size_t)c->K, sizeof(int32_t) * (size_t)c->K);
+    const int32_t* src = nkw_row_of(c, w);
+    if (!src) return LDAREF_ERR_OOM;
+    memcpy(row, src, sizeof(int32_t) * (size_t)c->K);
     return LDAREF_OK;
 }
 
@@ -673,8 +802,8 @@ int ldaref_get_alias_row(ldaref_ctx* c, int32_t w, uint32_t* split, uint32_t* al
     if (c->state != ST_ALIAS_VALID) return LDAREF_ERR_STATE;
     if (!word_is_dense(c, w)) return LDAREF_ERR_ARG;
     if (!c->built[w]) { int rc = build_word_table(c, w); if (rc) return rc; }
-    memcpy(split, c->split + (size_t)w * c->K, sizeof(uint32_t) * (size_t)c->K);
-    memcpy(alias, c->alias + (size_t)w * c->K, sizeof(uint32_t) * (size_t)c->K);
+    memcpy(split, c->split_row[w], sizeof(uint32_t) * (size_t)c->K);
+    memcpy(alias, c->alias_row[w], sizeof(uint32_t) * (size_t)c->K);
     *C = c->cap[w];
     return LDAREF_OK;
 }
