@@ -1,11 +1,13 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-The oracle cannot sweep 10^8..10^9 tokens in test time, so after an exhaustive
-comparison of the initial state (z, n_k) it is asked for the chains of sampled
-tokens only, for n_kw rows and alias tables of sampled words (the most frequent
-word -- many rebuild tiles -- and rare ones), and the GPU's post-sweep counts are
-checked against a numpy recount of the GPU's own assignment (a property that
-holds at any size).
+The oracle sweeps 10^8 tokens in half a minute (c2: every token is compared) but not 10^9,
+so for the larger workloads, after an exhaustive comparison of the initial state (z, n_k),
+it is asked for the chains of sampled tokens only, for n_kw rows and word-proposal tables
+of sampled words (the most frequent word -- many rebuild tiles --, words of every storage
+class, rare ones), and the GPU's post-sweep counts are checked against a numpy recount of
+the GPU's own assignment (a property that holds at any size).  Where the V x K table does
+not fit in host memory (c4, c5) the oracle counts a word's row when it is first needed
+(lazy_rows; pinned to the plain oracle in tests/test_oracle_storage.py).
 """
 import numpy as np
 import pytest
@@ -25,23 +27,38 @@ def lda_mod():
 
 
 def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12, seed=123,
-                  min_count=0):
-    """min_count > 0: words with fewer tokens draw from the mixture (bench.py's default form)."""
+                  min_count=0, dense_rows=0, lazy_rows=False):
+    """min_count > 0: words with fewer tokens draw from the mixture (bench.py's default form).
+    min_count < 0: bench.py's rule for the hybrid store -- dense tables only for words with at
+    least K tokens and more tokens than any word without a dense row.  dense_rows: as
+    lda_options (the oracle has no such notion: storage does not change a result)."""
     rng = np.random.default_rng(seed)
     doff, words = corpus.make_corpus(cfg)
     N = int(doff[-1])
+    freq = np.bincount(words, minlength=cfg.V)
+    if min_count < 0:
+        min_count = max(int(freq[max(dense_rows, 0):].max()) + 1, cfg.K)
     g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                    dense_alias_min_count=min_count)
+                    dense_rows=dense_rows, dense_alias_min_count=min_count)
     o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                          dense_alias_min_count=min_count, lazy_alias=True)
+                          dense_alias_min_count=min_count, lazy_alias=True, lazy_rows=lazy_rows)
     # initial state: exhaustive
     z_init = g.get_z()
     assert np.array_equal(z_init, o.get_z())
     assert np.array_equal(g.get_nk(), o.get_nk())
-    freq = np.bincount(words, minlength=cfg.V)
     order = np.argsort(-freq, kind="stable")
     sample_words = list(order[:3]) + list(order[[len(order) // 2, -1]]) + \
         list(rng.choice(cfg.V, n_words - 5, replace=False))
+    special = []   # words of every storage class of the hybrid store
+    if dense_rows != 0:
+        H = max(dense_rows, 0)
+        below = np.flatnonzero(freq[:H] < min_count)     # dense row, mixture table
+        if len(below):
+            special += [int(below[0]), int(below[len(below) // 2]), int(below[-1])]
+        tail = H + np.flatnonzero(freq[H:] > 0)          # sparse row (list + hash row)
+        special += [int(tail[0]), int(tail[len(tail) // 2]), int(tail[-1])]
+        special.append(int(H + np.argmax(freq[H:])))
+        sample_words += special
     for w in sample_words:
         assert np.array_equal(g.get_nkw_row(w), o.get_nkw_row(w)), "n_kw row %d" % w
     docs = rng.choice(cfg.D, 20, replace=False)
@@ -64,12 +81,13 @@ def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12,
         so, ao, co = o.get_alias_row(w)
         assert cg == co and np.array_equal(sg, so) and np.array_equal(ag, ao), "alias row %d" % w
     # the sweep: sampled chains (tokens of the hottest word, of rare words, uniform ones)
+    head = words[: 20_000_000]
     ids = np.unique(np.concatenate([
         rng.choice(N, n_tokens, replace=False),
-        np.flatnonzero(words[: 5_000_000] == order[0])[:200],
-        np.flatnonzero(words[: 5_000_000] == order[-1])[:50],
+        np.flatnonzero(head == order[0])[:200],
+        np.flatnonzero(words == order[-1])[:50],
         np.array([0, N - 1]),
-    ])).astype(np.int64)
+    ] + [np.flatnonzero(head == w)[:40] for w in special])).astype(np.int64)
     want = o.sweep_tokens(0, mh_steps, ids)
     g.sweep(mh_steps)
     z_new = g.get_z()
@@ -113,10 +131,87 @@ def test_c3_full_size_bench_configuration(lda_mod, oracle_mod):
     sampled_check(lda_mod, oracle_mod, cfg, 2, n_tokens=1500, n_words=10, min_count=cfg.K)
 
 
+@pytest.mark.timeout(900)
+def test_c2_full_size_every_token(lda_mod, oracle_mod):
+    """One whole iteration of c2 (9.9 * 10^7 tokens) against the oracle: every token's new
+    topic, n_k, sampled n_kw rows, and the log-likelihood before and after."""
+    cfg = corpus.CONFIGS["c2"]
+    doff, words = corpus.make_corpus(cfg)
+    rng = np.random.default_rng(11)
+    for min_count in (cfg.K,):      # the form bench.py times
+        g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                        dense_alias_min_count=min_count)
+        o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                              dense_alias_min_count=min_count, lazy_alias=True)
+        lg, lo = g.loglik(), o.loglik()
+        assert abs(lg[0] - lo[0]) <= 1e-9 * abs(lo[0]), (lg, lo)
+        g.build_alias(); o.build_alias()
+        g.sweep(cfg.mh_steps); o.sweep(cfg.mh_steps)
+        g.rebuild_counts(); o.rebuild_counts()
+        zg, zo = g.get_z(), o.get_z()
+        assert np.array_equal(zg, zo), "%d of %d tokens differ" % (int((zg != zo).sum()), len(zg))
+        assert np.array_equal(g.get_nk(), o.get_nk())
+        freq = np.bincount(words, minlength=cfg.V)
+        order = np.argsort(-freq, kind="stable")
+        for w in list(order[:5]) + list(order[[1000, 20000, -1]]) + list(rng.choice(cfg.V, 42, replace=False)):
+            assert np.array_equal(g.get_nkw_row(w), o.get_nkw_row(w)), "n_kw row %d" % w
+        lg, lo = g.loglik(), o.loglik()
+        assert abs(lg[0] - lo[0]) <= 1e-9 * abs(lo[0]), (lg, lo)
+        for a, b in zip(lg[1:], lo[1:]):
+            assert abs(a - b) <= 1e-9 * max(abs(b), abs(lo[0])), (lg, lo)
+        g.close()
+        o.close()
+
+
+@pytest.mark.timeout(900)
+def test_c3_loglik_and_every_token_on_600k_documents(lda_mod, oracle_mod):
+    """The first 600 000 documents of c3 (5.4 * 10^7 tokens, the benchmark's V and K): the
+    log-likelihood of 10^7..10^8 terms -- where the order of the block partial sums matters
+    most -- within 1e-9 of the oracle, before and after one whole iteration in the form
+    bench.py times, and every token of that iteration."""
+    cfg = corpus.scaled(corpus.CONFIGS["c3"], D=600_000)
+    doff, words = corpus.make_corpus(cfg)
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                    dense_alias_min_count=cfg.K)
+    o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                          dense_alias_min_count=cfg.K, lazy_alias=True, lazy_rows=True)
+    for it in range(2):
+        lg, lo = g.loglik(), o.loglik()
+        assert abs(lg[0] - lo[0]) <= 1e-9 * abs(lo[0]), (it, lg, lo)
+        for a, b in zip(lg[1:], lo[1:]):
+            assert abs(a - b) <= 1e-9 * max(abs(b), abs(lo[0])), (it, lg, lo)
+        if it == 1:
+            break
+        g.build_alias(); o.build_alias()
+        g.sweep(2); o.sweep(2)
+        g.rebuild_counts(); o.rebuild_counts()
+        zg, zo = g.get_z(), o.get_z()
+        assert np.array_equal(zg, zo), "%d of %d tokens differ" % (int((zg != zo).sum()), len(zg))
+        assert np.array_equal(g.get_nk(), o.get_nk())
+    g.close()
+    o.close()
+
+
+@pytest.mark.timeout(1100)
+def test_c4_full_size_sampled(lda_mod, oracle_mod):
+    """K = 100 000 on the hybrid store at full size (10^9 tokens, V = 10^6), as bench.py runs
+    it: sampled chains, rows, dense / mixture / shared tables and n_k against the oracle."""
+    cfg = corpus.CONFIGS["c4"]
+    sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10, min_count=-1,
+                  dense_rows=cfg.dense_rows, lazy_rows=True)
+
+
+@pytest.mark.timeout(1100)
+def test_c5_full_size_sampled(lda_mod, oracle_mod):
+    """One K = 10^6 slice with no dense row at full size (5 * 10^8 tokens)."""
+    cfg = corpus.CONFIGS["c5"]
+    sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10, min_count=-1,
+                  dense_rows=-1, lazy_rows=True)
+
+
 def property_check(lda_mod, cfg, dense_rows, mh_steps, seed=5):
-    """Workloads whose dense V x K table the oracle cannot hold: invariants and numpy
-    recounts of the GPU's own assignment (the sweep's chains are covered by the oracle at
-    the same K on small vocabularies in test_gpu_hybrid.py)."""
+    """Invariants and numpy recounts of the GPU's own assignment over two iterations of the
+    hybrid-store workloads (their chains, rows and tables meet the oracle in the tests above)."""
     rng = np.random.default_rng(seed)
     doff, words = corpus.make_corpus(cfg)
     N = int(doff[-1])
