@@ -92,7 +92,7 @@ void free_all(lda_ctx* c)
     c->side_stream = nullptr;
     dev_free(c, c->d_woff); dev_free(c, c->d_nkw); dev_free(c, c->d_nk);
     dev_free(c, c->d_alias); dev_free(c, c->d_cap); dev_free(c, c->d_chunk_doc); dev_free(c, c->d_tokdoc); dev_free(c, c->d_chunk_doc2); dev_free(c, c->d_tokdoc2); dev_free(c, c->d_long_doc);
-    dev_free(c, c->d_long_slot); dev_free(c, c->d_long_keys); dev_free(c, c->d_long_cnts);
+    dev_free(c, c->d_long_slot); dev_free(c, c->d_long_keys); dev_free(c, c->d_long_cnts); dev_free(c, c->d_long_first);
     dev_free(c, c->d_tiles); dev_free(c, c->d_multi_words); dev_free(c, c->d_partial); dev_free(c, c->d_row);
     dev_free(c, c->d_flag);
     dev_free(c, c->d_dense_alias_words);
@@ -480,6 +480,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_long_slot, (size_t)c->n_long + 1, "long document slots"));
     TRY(dev_alloc(c, &c->d_long_keys, (size_t)c->long_slots, "long document tables"));
     TRY(dev_alloc(c, &c->d_long_cnts, (size_t)c->long_slots, "long document tables"));
+    TRY(dev_alloc(c, &c->d_long_first, (size_t)c->long_slots, "long document tables"));
     c->n_partial = std::max(std::max(c->n_chunks, c->n_long), 4096);
     TRY(dev_alloc(c, &c->d_partial, (size_t)c->n_partial, "partial sums"));
     TRY(dev_alloc(c, &c->d_row, (size_t)K, "row staging"));

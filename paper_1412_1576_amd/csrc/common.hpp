@@ -109,6 +109,7 @@ struct lda_ctx {
     int64_t* d_long_slot = nullptr;    // [n_long+1] first hash slot of each long document
     int32_t* d_long_keys = nullptr;    // [total slots]
     int32_t* d_long_cnts = nullptr;
+    int32_t* d_long_first = nullptr;   // [total slots] log-likelihood: first token of every topic
     int32_t n_long = 0;
     int64_t long_slots = 0;
     std::vector<int32_t> h_long_doc;

@@ -112,6 +112,17 @@ struct GlobalDocTable {
         }
     }
 
+    // slot that holds topic k, which must be in the table
+    __device__ __forceinline__ uint32_t slot_of(int32_t k) const
+    {
+        uint32_t s = mulhi32(topic_hash(k), slots);
+        for (uint32_t n = 0; n < slots; ++n) {
+            if (ld(&keys[s]) == k) return s;
+            s = (s + 1 == slots) ? 0u : s + 1;
+        }
+        return 0;
+    }
+
     __device__ __forceinline__ int32_t count(int32_t k) const
     {
         uint32_t s = mulhi32(topic_hash(k), slots);

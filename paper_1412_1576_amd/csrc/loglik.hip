@@ -3,7 +3,13 @@
 //   doc  = sum_d [ lgG(K a) - lgG(L_d + K a) + sum_{k: n_kd>0} (lgG(n_kd + a) - lgG(a)) ]
 //   word = sum_k [ lgG(V b) - lgG(n_k + V b) ] + sum_{w,k: n_kw>0} (lgG(n_kw + b) - lgG(b))
 // fp64 throughout; every block reduces in a fixed tree and writes one partial,
-// the host adds the partials in index order with compensation.
+// the host adds the partials in index order with compensation.  Which slot of a document's
+// hash table a topic lands in depends on the order in which the threads' inserts win, so the
+// doc part is summed per token instead of per slot: the term of (document, topic) is added
+// by the first token of the document that has the topic.  Every run adds the same terms in
+// the same order and returns the same bits.
+#include <algorithm>
+
 #include "common.hpp"
 #include "doc_tile.hpp"
 
@@ -29,7 +35,7 @@ __device__ __forceinline__ double block_sum_f64(double v, double* wtot)
 __global__ __launch_bounds__(1024) void loglik_doc_tiles_kernel(
     const int32_t* __restrict__ z, const int32_t* __restrict__ doff,
     const int32_t* __restrict__ chunk_doc, const uint8_t* __restrict__ tokdoc, int32_t cap_tokens,
-    double alpha, double alphabar, double lg_alpha, double lg_alphabar,
+    int32_t cap_docs, double alpha, double alphabar, double lg_alpha, double lg_alphabar,
     double* __restrict__ partial)
 {
     extern __shared__ int32_t smem[];
@@ -39,11 +45,21 @@ __global__ __launch_bounds__(1024) void loglik_doc_tiles_kernel(
     double acc = 0.0;
     if (doff[d1] - doff[d0] <= cap_tokens) {
         const DocTile T = load_doc_tile(smem, cap_tokens, z, doff, tokdoc, d0, d1);
+        // first[s] = the lowest token of the tile whose topic sits in slot s
+        int32_t* first = smem + doc_tile_lds_bytes(cap_tokens, cap_docs) / sizeof(int32_t);
+        for (int32_t i = threadIdx.x; i < 2 * T.ntok; i += blockDim.x) first[i] = 0x7FFFFFFF;
+        __syncthreads();
+        auto slot_of = [&](int32_t i) {
+            const int32_t dl = tokdoc ? (int32_t)tokdoc[T.tok0 + i] : find_doc(T.sdoff, T.nd, i);
+            return 2 * T.sdoff[dl] + (int32_t)(T.zs[i] >> kTopicBits);
+        };
+        for (int32_t i = threadIdx.x; i < T.ntok; i += blockDim.x) atomicMin(&first[slot_of(i)], i);
+        __syncthreads();
         for (int32_t i = threadIdx.x; i < T.nd; i += blockDim.x)
             acc += lg_alphabar - lgamma((double)(T.sdoff[i + 1] - T.sdoff[i]) + alphabar);
-        for (int32_t i = threadIdx.x; i < 2 * T.ntok; i += blockDim.x) {
-            const uint32_t v = T.tab[i];
-            if (v != kEmptySlot) acc += lgamma((double)(v >> kTopicBits) + alpha) - lg_alpha;
+        for (int32_t i = threadIdx.x; i < T.ntok; i += blockDim.x) {
+            const int32_t s = slot_of(i);
+            if (first[s] == i) acc += lgamma((double)(T.tab[s] >> kTopicBits) + alpha) - lg_alpha;
         }
     }
     const double s = block_sum_f64(acc, wtot);
@@ -53,8 +69,8 @@ __global__ __launch_bounds__(1024) void loglik_doc_tiles_kernel(
 __global__ __launch_bounds__(1024) void loglik_long_docs_kernel(
     const int32_t* __restrict__ z, const int32_t* __restrict__ doff,
     const int32_t* __restrict__ long_doc, const int64_t* __restrict__ long_slot, int32_t* keys,
-    int32_t* cnts, double alpha, double alphabar, double lg_alpha, double lg_alphabar,
-    double* __restrict__ partial)
+    int32_t* cnts, int32_t* first_all, double alpha, double alphabar, double lg_alpha,
+    double lg_alphabar, double* __restrict__ partial)
 {
     __shared__ double wtot[16];
     const int32_t d = long_doc[blockIdx.x];
@@ -62,11 +78,20 @@ __global__ __launch_bounds__(1024) void loglik_long_docs_kernel(
     const int32_t L = doff[d + 1] - tok0;
     const int64_t s0 = long_slot[blockIdx.x];
     const GlobalDocTable tab = load_long_doc(keys + s0, cnts + s0, z + tok0, L);
+    // first[s] = the lowest token of the document whose topic sits in slot s
+    int32_t* first = first_all + s0;
+    for (uint32_t i = threadIdx.x; i < tab.slots; i += blockDim.x)
+        __hip_atomic_store(&first[i], 0x7FFFFFFF, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    for (int32_t i = threadIdx.x; i < L; i += blockDim.x) atomicMin(&first[tab.slot_of(z[tok0 + i])], i);
+    __syncthreads();
     double acc = 0.0;
     if (threadIdx.x == 0) acc += lg_alphabar - lgamma((double)L + alphabar);
-    for (uint32_t i = threadIdx.x; i < tab.slots; i += blockDim.x)
-        if (GlobalDocTable::ld(&tab.keys[i]) != kEmptyKey)
-            acc += lgamma((double)GlobalDocTable::ld(&tab.cnts[i]) + alpha) - lg_alpha;
+    for (int32_t i = threadIdx.x; i < L; i += blockDim.x) {
+        const uint32_t s = tab.slot_of(z[tok0 + i]);
+        if (GlobalDocTable::ld(&first[s]) == i)
+            acc += lgamma((double)GlobalDocTable::ld(&tab.cnts[s]) + alpha) - lg_alpha;
+    }
     const double s = block_sum_f64(acc, wtot);
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
@@ -124,85 +149,103 @@ __global__ __launch_bounds__(256) void loglik_sparse_kernel(const int32_t* __res
     if (threadIdx.x == 0) partial[blockIdx.x] = s;
 }
 
-// compensated (Neumaier) sum of the partials in index order
-double host_sum(const std::vector<double>& v, size_t n)
-{
+// compensated (Neumaier) sum, terms added in the order given
+struct CompensatedSum {
     double s = 0.0, comp = 0.0;
-    for (size_t i = 0; i < n; ++i) {
-        const double x = v[i], t = s + x;
+    void add(double x)
+    {
+        const double t = s + x;
         comp += (fabs(s) >= fabs(x)) ? (s - t) + x : (x - t) + s;
         s = t;
     }
-    return s + comp;
+    double value() const { return s + comp; }
+};
+
+// Sum of the n partials at d_partial in index order.  Staged through `host` (a buffer of
+// host_cap doubles owned by the caller) a piece at a time, so the result does not depend on
+// host_cap.  Waits for the stream.
+int sum_partials(lda_ctx* c, const double* d_partial, size_t n, double* host, size_t host_cap,
+                 double* out)
+{
+    CompensatedSum acc;
+    for (size_t i0 = 0; i0 < n; i0 += host_cap) {
+        const size_t m = (n - i0 < host_cap) ? n - i0 : host_cap;
+        LDA_HIP(c, hipMemcpyAsync(host, d_partial + i0, sizeof(double) * m, hipMemcpyDeviceToHost,
+                                  c->stream));
+        LDA_HIP(c, hipStreamSynchronize(c->stream));
+        for (size_t i = 0; i < m; ++i) acc.add(host[i]);
+    }
+    *out = acc.value();
+    return LDA_OK;
 }
 
-}  // namespace
-
-int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
+// The log-likelihood with the partial sums in d_partial (device memory of at least
+// max(n_chunks, n_long, 4096) doubles) and host staging in `h` (h_cap doubles).
+int run_loglik(lda_ctx* c, double* d_partial, double* h, size_t h_cap, double* doc_part,
+               double* word_part)
 {
     const double lga = lgamma(c->alpha), lgab = lgamma(c->alphabar);
     const double lgb = lgamma(c->beta), lgbb = lgamma(c->betabar);
-    std::vector<double> h((size_t)c->n_partial);
-    double doc = 0.0, word = 0.0;
+    double doc = 0.0, word = 0.0, part = 0.0;
+    int rc;
 
     if (c->n_chunks > 0) {
-        const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
+        const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs) +
+                           sizeof(int32_t) * 2 * (size_t)c->chunk_tokens;
         if (lds > 48 * 1024)
             LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(loglik_doc_tiles_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         hipLaunchKernelGGL(loglik_doc_tiles_kernel, dim3(c->n_chunks), dim3(c->sweep_block), lds,
                            c->stream, c->d_z, c->d_doff, c->d_chunk_doc, c->d_tokdoc, c->chunk_tokens,
-                           c->alpha, c->alphabar, lga, lgab, c->d_partial);
+                           c->chunk_docs, c->alpha, c->alphabar, lga, lgab, d_partial);
         LDA_HIP(c, hipGetLastError());
-        LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * c->n_chunks,
-                                  hipMemcpyDeviceToHost, c->stream));
-        LDA_HIP(c, hipStreamSynchronize(c->stream));
-        doc += host_sum(h, (size_t)c->n_chunks);
+        if ((rc = sum_partials(c, d_partial, (size_t)c->n_chunks, h, h_cap, &part)) != LDA_OK) return rc;
+        doc += part;
     }
     if (c->n_long > 0) {
         hipLaunchKernelGGL(loglik_long_docs_kernel, dim3(c->n_long), dim3(1024), 0, c->stream,
                            c->d_z, c->d_doff, c->d_long_doc, c->d_long_slot, c->d_long_keys,
-                           c->d_long_cnts, c->alpha, c->alphabar, lga, lgab, c->d_partial);
+                           c->d_long_cnts, c->d_long_first, c->alpha, c->alphabar, lga, lgab, d_partial);
         LDA_HIP(c, hipGetLastError());
-        LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * c->n_long,
-                                  hipMemcpyDeviceToHost, c->stream));
-        LDA_HIP(c, hipStreamSynchronize(c->stream));
-        doc += host_sum(h, (size_t)c->n_long);
+        if ((rc = sum_partials(c, d_partial, (size_t)c->n_long, h, h_cap, &part)) != LDA_OK) return rc;
+        doc += part;
     }
     {
         const int blocks = 4096;
         const int64_t dense_rows = c->hybrid ? c->H : c->V;
         if (dense_rows > 0) {
             hipLaunchKernelGGL(loglik_word_kernel, dim3(blocks), dim3(256), 0, c->stream, c->d_nkw,
-                               dense_rows * (int64_t)c->K, c->beta, lgb, c->d_partial);
+                               dense_rows * (int64_t)c->K, c->beta, lgb, d_partial);
             LDA_HIP(c, hipGetLastError());
-            LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * blocks,
-                                      hipMemcpyDeviceToHost, c->stream));
-            LDA_HIP(c, hipStreamSynchronize(c->stream));
-            word += host_sum(h, blocks);
+            if ((rc = sum_partials(c, d_partial, blocks, h, h_cap, &part)) != LDA_OK) return rc;
+            word += part;
         }
         if (c->hybrid && c->n_sparse > 0) {
             hipLaunchKernelGGL(loglik_sparse_kernel, dim3(blocks), dim3(256), 0, c->stream,
                                c->d_sparse_words, c->n_sparse, c->d_sp_off, c->d_sp_count,
-                               c->d_sp_nnz, c->beta, lgb, c->d_partial);
+                               c->d_sp_nnz, c->beta, lgb, d_partial);
             LDA_HIP(c, hipGetLastError());
-            LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * blocks,
-                                      hipMemcpyDeviceToHost, c->stream));
-            LDA_HIP(c, hipStreamSynchronize(c->stream));
-            word += host_sum(h, blocks);
+            if ((rc = sum_partials(c, d_partial, blocks, h, h_cap, &part)) != LDA_OK) return rc;
+            word += part;
         }
         const int kb = 64;
         hipLaunchKernelGGL(loglik_nk_kernel, dim3(kb), dim3(256), 0, c->stream, c->d_nk, c->K,
-                           c->betabar, lgbb, c->d_partial);
+                           c->betabar, lgbb, d_partial);
         LDA_HIP(c, hipGetLastError());
-        LDA_HIP(c, hipMemcpyAsync(h.data(), c->d_partial, sizeof(double) * kb,
-                                  hipMemcpyDeviceToHost, c->stream));
-        LDA_HIP(c, hipStreamSynchronize(c->stream));
-        word += host_sum(h, kb);
+        if ((rc = sum_partials(c, d_partial, kb, h, h_cap, &part)) != LDA_OK) return rc;
+        word += part;
     }
     *doc_part = doc;
     *word_part = word;
     return LDA_OK;
+}
+
+}  // namespace
+
+int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
+{
+    std::vector<double> h((size_t)c->n_partial);
+    return run_loglik(c, c->d_partial, h.data(), h.size(), doc_part, word_part);
 }
 
 }  // namespace lda
