@@ -156,6 +156,23 @@ int lda_rebuild_counts(lda_ctx* ctx);
  */
 int lda_loglik(lda_ctx* ctx, double* total, double* doc_part, double* word_part);
 
+/*
+ * lda_loglik_noalloc -- lda_loglik for callers that cannot allocate: code under HIP graph
+ * capture around it, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels, same summation order and therefore the same value as lda_loglik; the
+ * per-block partial sums go to a static device array of the library (2^20 doubles = 8 MB,
+ * held by every GPU the library runs on until the process ends) instead of the context's
+ * own buffer, and the host side stages them through the stack.  The call makes no device or
+ * host allocation.  The context's device must be the current device.
+ *   - LDA_ERR_UNSUPPORTED when the context needs more partial sums than the array holds
+ *     (one per document tile: more than 2^20 tiles, or long documents); use lda_loglik then.
+ *   - All contexts on one GPU share the array: two calls that overlap on one GPU (two
+ *     host threads, two streams) race on it and must be serialised by the caller.  Nothing in
+ *     the array needs to be zero on entry; every element that is read was written by the
+ *     same call.
+ */
+int lda_loglik_noalloc(lda_ctx* ctx, double* total, double* doc_part, double* word_part);
+
 /* ---- accessors (parity checks, checkpoint / warm start of Sec. 6); all synchronise ---- */
 int64_t lda_num_tokens(const lda_ctx* ctx);
 int64_t lda_sweep_index(const lda_ctx* ctx);

@@ -9,6 +9,7 @@
 // by the first token of the document that has the topic.  Every run adds the same terms in
 // the same order and returns the same bits.
 #include <algorithm>
+#include <mutex>
 
 #include "common.hpp"
 #include "doc_tile.hpp"
@@ -179,6 +180,34 @@ int sum_partials(lda_ctx* c, const double* d_partial, size_t n, double* host, si
     return LDA_OK;
 }
 
+// Scratch of lda_loglik_noalloc: the per-block partial sums of the kernels above.  One copy
+// of the array per GPU, at an address that hipGetSymbolAddress reports for the current
+// device; host code uses that address, never the array's name.
+constexpr size_t kStaticPartials = (size_t)1 << 20;  // 8 MB
+static __device__ __align__(256) double g_static_partials[kStaticPartials];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of g_static_partials on the current device (looked up once per device).
+int static_partials(lda_ctx* c, double** out)
+{
+    int dev = -1;
+    LDA_HIP(c, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(c, LDA_ERR_UNSUPPORTED, "lda_loglik_noalloc: device index %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        LDA_HIP(c, hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_partials)));
+        if (!p) return fail(c, LDA_ERR_HIP, "lda_loglik_noalloc: no address for the static scratch");
+        g_scratch_ptr[dev] = static_cast<double*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return LDA_OK;
+}
+
 // The log-likelihood with the partial sums in d_partial (device memory of at least
 // max(n_chunks, n_long, 4096) doubles) and host staging in `h` (h_cap doubles).
 int run_loglik(lda_ctx* c, double* d_partial, double* h, size_t h_cap, double* doc_part,
@@ -249,3 +278,29 @@ int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
 }
 
 }  // namespace lda
+
+using namespace lda;
+
+extern "C" int lda_loglik_noalloc(lda_ctx* c, double* total, double* doc_part, double* word_part)
+{
+    if (!c) return LDA_ERR_ARG;
+    if (!total) return fail(c, LDA_ERR_ARG, "lda_loglik_noalloc: total is NULL");
+    if (c->state != COUNTS_VALID && c->state != ALIAS_VALID)
+        return fail(c, LDA_ERR_STATE, "lda_loglik_noalloc: counts are stale (call lda_rebuild_counts)");
+    const size_t need = (size_t)std::max(std::max(c->n_chunks, c->n_long), 4096);
+    if (need > kStaticPartials)
+        return fail(c, LDA_ERR_UNSUPPORTED,
+                    "lda_loglik_noalloc: %zu partial sums (one per document tile) exceed the static "
+                    "scratch of %zu; use lda_loglik", need, kStaticPartials);
+    double* scratch = nullptr;
+    int rc = static_partials(c, &scratch);
+    if (rc != LDA_OK) return rc;
+    double staging[2048];  // host side: on the stack
+    double d = 0.0, w = 0.0;
+    rc = run_loglik(c, scratch, staging, sizeof(staging) / sizeof(staging[0]), &d, &w);
+    if (rc != LDA_OK) return rc;
+    if (doc_part) *doc_part = d;
+    if (word_part) *word_part = w;
+    *total = d + w;
+    return LDA_OK;
+}
