@@ -76,10 +76,11 @@ void free_all(lda_ctx* c)
     dev_free(c, c->d_word); dev_free(c, c->d_doff); dev_free(c, c->d_z); dev_free(c, c->d_znew);
     dev_free(c, c->d_gid); dev_free(c, c->d_wpos); dev_free(c, c->d_xmap); dev_free(c, c->d_zt); dev_free(c, c->d_rec);
     dev_free(c, c->d_row_items); dev_free(c, c->d_mix_items); dev_free(c, c->d_gather_pieces);
-    dev_free(c, c->d_sort_keys);
-    dev_free(c, c->d_sp_wloc); dev_free(c, c->d_sp_keys); dev_free(c, c->d_sp_sorted); dev_free(c, c->d_sp_runlen);
-    dev_free(c, c->d_sp_first); dev_free(c, c->d_sp_nruns);
-    dev_free(c, c->d_sp_tmp); dev_free(c, c->d_sort_tmp);
+    for (int i = 0; i < 3; ++i) dev_free(c, c->d_sort_words[i]);
+    dev_free(c, c->d_long_words); dev_free(c, c->d_long_base); dev_free(c, c->d_long_tiles); dev_free(c, c->d_fill_tiles);
+    dev_free(c, c->d_long_part); dev_free(c, c->d_long_dcount); dev_free(c, c->d_long_dstart);
+    dev_free(c, c->d_long_cursor); dev_free(c, c->d_long_nnzd); dev_free(c, c->d_long_lofs);
+    dev_free(c, c->d_nk_part); dev_free(c, c->d_nk_tiles); dev_free(c, c->d_nk_ranges);
     for (hipEvent_t& e : c->pass_ev) {
         if (e) (void)hipEventDestroy(e);
         e = nullptr;
@@ -220,7 +221,6 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
         if (list_total > 0x7FFFFFFFull || hash_total > 0xFFFFFFFFull)
             return fail(c, LDA_ERR_UNSUPPORTED, "lda_init: sparse rows exceed 2^31 entries");
     }
-    c->h_sparse_p0 = woff[H];
     c->h_sp_off[V] = (uint32_t)list_total;
     c->h_hs_off[V] = (uint32_t)hash_total;
     c->total_list = (int64_t)list_total;
@@ -274,7 +274,7 @@ int setup_hybrid(lda_ctx* c, const std::vector<int32_t>& woff)
         AL(d_big_ws, c->big_ws_stride * ((size_t)c->n_big_wg + 1), "table workspace");
     }
 #undef AL
-    return LDA_OK;
+    return setup_sparse_rows(c, woff);
 }
 
 

@@ -34,6 +34,13 @@ struct RebuildTile {
                     // 3: single tile of a list-only word (kKindListOnly): the list, not the row
 };
 
+// A tile of a partition pass (sparse_rows.hip): source positions [p0, p1) of segment seg (a
+// long word, or the whole of z)
+struct PartTile {
+    int32_t seg;
+    int32_t p0, p1;
+};
+
 }  // namespace lda
 
 struct lda_ctx {
@@ -161,21 +168,30 @@ struct lda_ctx {
                                          // bit 2 (kKindListOnly): the dense row is allotted but
                                          // not kept -- see kKindListOnly
     std::vector<uint32_t> h_sp_off, h_hs_off;
+    // sparse-row rebuild (sparse_rows.hip): words sorted in LDS, in three size classes; longer
+    // words partitioned by topic range in d_long_part (segment of long word i at d_long_base[i])
+    int32_t* d_sort_words[3] = {};
+    int32_t n_sort_words[3] = {};
+    int32_t* d_long_words = nullptr;
+    uint32_t* d_long_base = nullptr;
+    lda::PartTile* d_long_tiles = nullptr;
+    lda::PartTile* d_fill_tiles = nullptr;  // tiles over the places of the long words' lists
+    int32_t n_long_words = 0, n_long_tiles = 0, n_fill_tiles = 0;
+    uint32_t long_word_tokens = 0;
+    uint32_t max_hash_row = 0;           // slots of the largest hash row that is filled by atomics
+    bool clear_all_hash_rows = false;    // those rows own most of d_hs: clear it in one go
+    int32_t* d_long_part = nullptr;
+    uint32_t* d_long_dcount = nullptr;   // [n_long_words * ranges] tokens per range (zero between rebuilds)
+    uint32_t* d_long_dstart = nullptr;   // [n_long_words * (ranges + 1)]
+    uint32_t* d_long_cursor = nullptr;
+    uint32_t* d_long_nnzd = nullptr;     // non-zero topics per range
+    uint32_t* d_long_lofs = nullptr;     // their exclusive prefix: list position of a range
+    // n_k for very large K: z partitioned by topic range
+    int32_t* d_nk_part = nullptr;
+    lda::PartTile* d_nk_tiles = nullptr;
+    int32_t n_nk_tiles = 0;
+    uint32_t* d_nk_ranges = nullptr;
     // scratch
-    // sparse rows by one global sort (layout.hip): word index of every sparse-row token, keys,
-    // sorted keys, run lengths, first run of every word, number of runs
-    uint32_t* d_sp_wloc = nullptr;
-    uint64_t* d_sp_keys = nullptr;
-    uint64_t* d_sp_sorted = nullptr;
-    uint32_t* d_sp_runlen = nullptr;
-    int32_t* d_sp_first = nullptr;
-    int32_t* d_sp_nruns = nullptr;
-    void* d_sp_tmp = nullptr;
-    size_t sp_tmp_bytes = 0;
-    int64_t h_sparse_p0 = 0;           // word-major position of the first sparse-row token
-    int32_t* d_sort_keys = nullptr;    // [N] sorted copy of z (n_k by sorting, very large K)
-    void* d_sort_tmp = nullptr;
-    size_t sort_tmp_bytes = 0;
     double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
     int32_t n_partial = 0;
     int32_t* d_row = nullptr;          // [max(K,1)] row staging for accessors
@@ -275,8 +291,9 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sweep_split(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
-int launch_nk_by_sort(lda_ctx* c);
-int launch_sparse_lists_by_sort(lda_ctx* c);  // lists of the sparse-row words; first runs in d_sp_first  // n_k from a radix sort of z (K too large for LDS histograms)
+int setup_sparse_rows(lda_ctx* c, const std::vector<int32_t>& woff);
+int launch_sparse_rows(lda_ctx* c);   // lists, list lengths and hash rows of the sparse-row words
+int launch_nk_by_ranges(lda_ctx* c);  // n_k when K is too large for a few LDS histograms over z
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
 int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
 int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo, int32_t hi,

@@ -5,7 +5,6 @@
 #include <cstring>
 
 #include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_run_length_encode.hpp>
 
 #include "common.hpp"
 
@@ -88,133 +87,6 @@ __global__ __launch_bounds__(256) void compose_kernel(int32_t* __restrict__ wpos
         wpos[g] = xmap[wpos[g]];
 }
 
-// n_k[k] = number of entries equal to k in the ascending array `sorted`
-__global__ __launch_bounds__(256) void nk_from_sorted_kernel(const int32_t* __restrict__ sorted,
-                                                             int64_t n, int32_t K,
-                                                             int32_t* __restrict__ nk)
-{
-    const int32_t k = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (k >= K) return;
-    int64_t bound[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {  // first position whose key is >= k + j
-        int64_t lo = 0, hi = n;
-        while (lo < hi) {
-            const int64_t mid = (lo + hi) >> 1;
-            if (sorted[mid] < k + j) lo = mid + 1; else hi = mid;
-        }
-        bound[j] = lo;
-    }
-    nk[k] = (int32_t)(bound[1] - bound[0]);
-}
-
-// ---- sparse rows by one global sort (words without a dense row are the ids >= H, so their
-// tokens are the word-major positions [p0, N)) ---------------------------------------------
-
-// wloc[i] = (word of position p0 + i) - H: the last w >= H with woff[w] <= p0 + i
-__global__ __launch_bounds__(256) void sparse_wloc_kernel(const int32_t* __restrict__ woff, int32_t H,
-                                                          int32_t V, int64_t p0, int64_t n,
-                                                          uint32_t* __restrict__ wloc)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t p = p0 + i;
-        int32_t lo = H, hi = V;  // woff[lo] <= p < woff[hi]
-        while (hi - lo > 1) {
-            const int32_t mid = lo + ((hi - lo) >> 1);
-            if (woff[mid] <= p) lo = mid; else hi = mid;
-        }
-        wloc[i] = (uint32_t)(lo - H);
-    }
-}
-
-// key = (word - H) << tb | topic
-__global__ __launch_bounds__(256) void sparse_keys_kernel(const int32_t* __restrict__ zt, int32_t sh,
-                                                          uint32_t zmask,
-                                                          const uint32_t* __restrict__ wloc,
-                                                          int64_t p0, int64_t n, int32_t tb,
-                                                          const int32_t* __restrict__ xmap,
-                                                          uint64_t* __restrict__ keys)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const size_t q = xmap ? (size_t)xmap[p0 + i] : (size_t)(p0 + i);
-        keys[i] = ((uint64_t)wloc[i] << tb) | (uint64_t)((uint32_t)zt[q << sh] & zmask);
-    }
-}
-
-// first[wl] = index of the first run (distinct key) of word H + wl, wl = 0..n_words
-__global__ __launch_bounds__(256) void sparse_first_run_kernel(const uint64_t* __restrict__ uniq,
-                                                               const int32_t* __restrict__ n_runs,
-                                                               int32_t n_words, int32_t tb,
-                                                               int32_t* __restrict__ first)
-{
-    const int32_t wl = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (wl > n_words) return;
-    const uint64_t key = (uint64_t)wl << tb;
-    int32_t lo = 0, hi = *n_runs;
-    while (lo < hi) {
-        const int32_t mid = lo + ((hi - lo) >> 1);
-        if (uniq[mid] < key) lo = mid + 1; else hi = mid;
-    }
-    first[wl] = lo;
-}
-
-// run r is entry r - first[word] of its word's list; it also goes into the word's hash row
-// (cleared beforehand), one thread per entry so that a word with a million entries is
-// filled by as many threads
-__global__ __launch_bounds__(256) void sparse_lists_kernel(const uint64_t* __restrict__ uniq,
-                                                           const uint32_t* __restrict__ counts,
-                                                           const int32_t* __restrict__ n_runs,
-                                                           const int32_t* __restrict__ first,
-                                                           int32_t tb, int32_t H,
-                                                           const uint32_t* __restrict__ sp_off,
-                                                           int32_t* __restrict__ sp_topic,
-                                                           int32_t* __restrict__ sp_count,
-                                                           const uint32_t* __restrict__ hs_off,
-                                                           uint2* __restrict__ hs)
-{
-    const int64_t nr = *n_runs;
-    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r < nr;
-         r += (int64_t)gridDim.x * blockDim.x) {
-        const uint64_t key = uniq[r];
-        const uint32_t wl = (uint32_t)(key >> tb);
-        const int32_t w = H + (int32_t)wl;
-        const int32_t topic = (int32_t)(key & ((1ull << tb) - 1ull));
-        const uint32_t count = counts[r];
-        const size_t pos = (size_t)sp_off[w] + (size_t)(r - first[wl]);
-        sp_topic[pos] = topic;
-        sp_count[pos] = (int32_t)count;
-        uint2* __restrict__ row = hs + hs_off[w];
-        const uint32_t cap = hs_off[w + 1] - hs_off[w];  // a power of two, at least twice the entries
-        const uint32_t lg = 31u - (uint32_t)__clz((int)cap);
-        uint32_t slot = row_hash_slot(topic, lg);
-        for (uint32_t i = 0; i < cap; ++i) {
-            if (atomicCAS(&row[slot].x, 0xFFFFFFFFu, (uint32_t)topic) == 0xFFFFFFFFu) {
-                row[slot].y = count;
-                break;
-            }
-            slot = (slot + 1) & (cap - 1);
-        }
-    }
-}
-
-// list lengths from the first-run indices
-__global__ __launch_bounds__(256) void sparse_nnz_kernel(const int32_t* __restrict__ first,
-                                                         int32_t n_words, int32_t H,
-                                                         int32_t* __restrict__ sp_nnz)
-{
-    const int32_t wl = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
-    if (wl < n_words) sp_nnz[H + wl] = first[wl + 1] - first[wl];
-}
-
-__global__ __launch_bounds__(256) void clear_hash_kernel(uint2* __restrict__ hs, int64_t n)
-{
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x)
-        hs[i] = make_uint2(0xFFFFFFFFu, 0u);
-}
-
 unsigned grid_for(int64_t n, int block, unsigned cap = 8192)
 {
     int64_t b = (n + block - 1) / block;
@@ -236,95 +108,6 @@ int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo,
     LDA_HIP(c, hipMemcpyAsync(&bad, c->d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     LDA_HIP(c, hipStreamSynchronize(c->stream));
     *ok = (bad == 0);
-    return LDA_OK;
-}
-
-// n_k for K beyond what LDS histograms cover in a few passes over z: radix sort of z, then
-// the run length of every topic by bisection.  (One global atomic per token, the
-// alternative, runs at about 27 G atomics/s: 18.6 ms for 5e8 tokens against 5 ms for this.)
-int launch_nk_by_sort(lda_ctx* c)
-{
-    const int64_t N = c->N;
-    int end_bit = 1;
-    while (end_bit < 31 && (1LL << end_bit) < (long long)c->K) ++end_bit;
-    if (!c->d_sort_keys) {
-        size_t bytes = 0;
-        LDA_HIP(c, rocprim::radix_sort_keys(nullptr, bytes, c->d_z, c->d_z, (size_t)N, 0u,
-                                            (unsigned)end_bit, c->stream));
-        LDA_ALLOC(c, &c->d_sort_keys, N, "sorted topics");
-        LDA_ALLOC(c, reinterpret_cast<unsigned char**>(&c->d_sort_tmp), bytes, "sort workspace");
-        c->sort_tmp_bytes = bytes;
-    }
-    size_t bytes = c->sort_tmp_bytes;
-    LDA_HIP(c, rocprim::radix_sort_keys(c->d_sort_tmp, bytes, c->d_z, c->d_sort_keys, (size_t)N, 0u,
-                                        (unsigned)end_bit, c->stream));
-    hipLaunchKernelGGL(nk_from_sorted_kernel, dim3((c->K + 255) / 256), dim3(256), 0, c->stream,
-                       c->d_sort_keys, N, c->K, c->d_nk);
-    LDA_HIP(c, hipGetLastError());
-    return LDA_OK;
-}
-
-// Sorted (topic, count) lists, their lengths and the hash rows of every word without a dense
-// row, from one radix sort of (word, topic) keys over their tokens and a run-length encoding.
-int launch_sparse_lists_by_sort(lda_ctx* c)
-{
-    const int32_t H = c->H, V = c->V, n_words = V - H;
-    const int64_t p0 = c->h_sparse_p0, n = c->N - p0;
-    if (n_words <= 0) return LDA_OK;
-    int tb = 1, wb = 1;
-    while (tb < 31 && (1LL << tb) < (long long)c->K) ++tb;
-    while (wb < 31 && (1LL << wb) < (long long)n_words) ++wb;
-    if (!c->d_sp_first) {
-        LDA_ALLOC(c, &c->d_sp_first, (size_t)n_words + 2, "first runs");
-        LDA_ALLOC(c, &c->d_sp_nruns, 2, "run count");
-        LDA_HIP(c, hipMemsetAsync(c->d_sp_nruns, 0, sizeof(int32_t) * 2, c->stream));
-        const size_t m = (size_t)(n > 0 ? n : 1);
-        LDA_ALLOC(c, &c->d_sp_wloc, m, "tail word indices");
-        LDA_ALLOC(c, &c->d_sp_keys, m, "(word, topic) keys");
-        LDA_ALLOC(c, &c->d_sp_sorted, m, "sorted keys");
-        LDA_ALLOC(c, &c->d_sp_runlen, m, "run lengths");
-        size_t b1 = 0, b2 = 0;
-        LDA_HIP(c, rocprim::radix_sort_keys(nullptr, b1, c->d_sp_keys, c->d_sp_sorted, (size_t)n, 0u,
-                                            (unsigned)(tb + wb), c->stream));
-        LDA_HIP(c, rocprim::run_length_encode(nullptr, b2, c->d_sp_sorted, (size_t)n, c->d_sp_keys,
-                                              c->d_sp_runlen, c->d_sp_nruns, c->stream));
-        c->sp_tmp_bytes = b1 > b2 ? b1 : b2;
-        LDA_ALLOC(c, reinterpret_cast<unsigned char**>(&c->d_sp_tmp), c->sp_tmp_bytes, "sort workspace");
-        if (n > 0) {
-            hipLaunchKernelGGL(sparse_wloc_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream,
-                               c->d_woff, H, V, p0, n, c->d_sp_wloc);
-            LDA_HIP(c, hipGetLastError());
-        }
-    }
-    if (n > 0) {
-        hipLaunchKernelGGL(sparse_keys_kernel, dim3(grid_for(n, 256)), dim3(256), 0, c->stream, c->d_zt,
-                           c->zt_shift, c->zt_mask, c->d_sp_wloc, p0, n, tb, c->d_xmap, c->d_sp_keys);
-        LDA_HIP(c, hipGetLastError());
-        size_t bytes = c->sp_tmp_bytes;
-        LDA_HIP(c, rocprim::radix_sort_keys(c->d_sp_tmp, bytes, c->d_sp_keys, c->d_sp_sorted, (size_t)n,
-                                            0u, (unsigned)(tb + wb), c->stream));
-        bytes = c->sp_tmp_bytes;
-        // the distinct keys overwrite the unsorted ones
-        LDA_HIP(c, rocprim::run_length_encode(c->d_sp_tmp, bytes, c->d_sp_sorted, (size_t)n,
-                                              c->d_sp_keys, c->d_sp_runlen, c->d_sp_nruns, c->stream));
-    }
-    hipLaunchKernelGGL(sparse_first_run_kernel, dim3((n_words + 1 + 255) / 256), dim3(256), 0, c->stream,
-                       c->d_sp_keys, c->d_sp_nruns, n_words, tb, c->d_sp_first);
-    LDA_HIP(c, hipGetLastError());
-    hipLaunchKernelGGL(sparse_nnz_kernel, dim3((n_words + 255) / 256), dim3(256), 0, c->stream,
-                       c->d_sp_first, n_words, H, c->d_sp_nnz);
-    LDA_HIP(c, hipGetLastError());
-    if (c->total_hash > 0) {
-        hipLaunchKernelGGL(clear_hash_kernel, dim3(grid_for(c->total_hash, 256, 65536)), dim3(256), 0,
-                           c->stream, c->d_hs, c->total_hash);
-        LDA_HIP(c, hipGetLastError());
-    }
-    if (n > 0) {
-        hipLaunchKernelGGL(sparse_lists_kernel, dim3(grid_for(n, 256, 65536)), dim3(256), 0, c->stream,
-                           c->d_sp_keys, c->d_sp_runlen, c->d_sp_nruns, c->d_sp_first, tb, H, c->d_sp_off,
-                           c->d_sp_topic, c->d_sp_count, c->d_hs_off, c->d_hs);
-        LDA_HIP(c, hipGetLastError());
-    }
     return LDA_OK;
 }
 

@@ -6,8 +6,8 @@
 // then histograms a tile of a segment in LDS and writes the dense row.  Words whose segment is longer than one tile are split
 // over several workgroups whose partial histograms are merged into a
 // pre-zeroed row with integer atomics (order-free, hence exact).
-// n_k: an LDS-privatised histogram of z over all tokens (a radix sort of z for very large K,
-// layout.hip).
+// n_k: an LDS-privatised histogram of z over all tokens (for very large K over a copy of z
+// partitioned by topic range, sparse_rows.hip).
 #include "common.hpp"
 #include "xcd.hpp"
 
@@ -275,8 +275,8 @@ int launch_rebuild(lda_ctx* c)
 
 // Hybrid store (LightLDA Sec. 5): dense rows for the head words as above; for every other word
 // a list of its non-zero (topic, count) pairs in ascending topic order plus an open-addressing
-// hash row (load <= 1/2) for random lookups, both made from one global sort of the tail
-// words' (word, topic) keys (layout.hip).
+// hash row (load <= 1/2) for random lookups, both made word by word from the word's own
+// segment of the word-major order (sparse_rows.hip).
 int launch_rebuild_hybrid(lda_ctx* c)
 {
     const int32_t K = c->K;
@@ -285,13 +285,13 @@ int launch_rebuild_hybrid(lda_ctx* c)
         const int rc = launch_dense_rows(c);
         if (rc != LDA_OK) return rc;
     }
-    // ---- sparse rows: lists, lengths and hash rows by one global sort (layout.hip) ----
+    // ---- sparse rows: lists, lengths and hash rows (sparse_rows.hip) ----
     if (c->V > c->H) {
-        const int rc = launch_sparse_lists_by_sort(c);
+        const int rc = launch_sparse_rows(c);
         if (rc != LDA_OK) return rc;
     }
     // ---- n_k ----
-    if (K > 8 * kNkRangeTopics) return launch_nk_by_sort(c);
+    if (K > 8 * kNkRangeTopics) return launch_nk_by_ranges(c);
     return launch_nk_hist(c);
 }
 
