@@ -57,14 +57,17 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
-def cpu_baseline(cfg, doff, words, mh_steps, sample_docs, dense_alias_min_count=0):
-    """The oracle as it stands on the first `sample_docs` documents (same V, K)."""
+def cpu_baseline(cfg, doff, words, mh_steps, sample_docs, dense_alias_min_count=0, lazy_rows=False):
+    """The oracle as it stands on the first `sample_docs` documents (same V, K).  lazy_rows: the
+    oracle counts a word's n_kw row when it first needs it (workloads whose V x K table does
+    not fit in host memory)."""
     import oracle
     D = min(sample_docs, len(doff) - 1)
     sdoff = np.ascontiguousarray(doff[: D + 1])
     swords = np.ascontiguousarray(words[: int(sdoff[-1])])
     o = oracle.Oracle(sdoff, swords, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                      dense_alias_min_count=dense_alias_min_count, lazy_alias=True)
+                      dense_alias_min_count=dense_alias_min_count, lazy_alias=True,
+                      lazy_rows=lazy_rows)
     t0 = time.perf_counter()
     o.build_alias()
     o.sweep(mh_steps)
@@ -73,10 +76,80 @@ def cpu_baseline(cfg, doff, words, mh_steps, sample_docs, dense_alias_min_count=
     n = o.N
     o.close()
     return {
-        "value": n / dt, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+        "value": n / dt, "unit": "tokens/s", "cores": 1, "host_cores": os.cpu_count(),
+        "kind": "oracle",
         "sample": "first %d documents (%d tokens) of the same corpus, same V and K; one full "
-                  "iteration (alias tables of the words that occur, sweep, recount), %.1f s"
-                  % (D, n, dt),
+                  "iteration (alias tables of the words that occur, sweep, recount) on 1 of the "
+                  "host's %d cores, %.1f s" % (D, n, os.cpu_count(), dt),
+    }
+
+
+CPU_SAMPLE_DOCS = {"c1": 1000, "c2": 60000, "c3": 600000, "c4": 10000, "c5": 1000}
+
+
+def store_options(workload, cfg, words, dense_alias_min_count):
+    """lda_options of a workload and a description of its n_kw store.  c4: dense rows for the
+    head words; c5: no dense row; every word without a dense row draws from the mixture.
+    c1-c3: dense rows, and the mixture below `dense_alias_min_count` tokens (-1: K; 0: a dense
+    table for every word)."""
+    if workload in ("c4", "c5"):
+        dense_rows = cfg.dense_rows if workload == "c4" else -1
+        cnt = np.bincount(words, minlength=cfg.V)
+        tail = cnt[max(dense_rows, 0):]
+        # dense K-bin tables only for words with at least K tokens (rows that can be dense)
+        opts = dict(dense_rows=dense_rows, dense_alias_min_count=max(int(tail.max()) + 1, cfg.K))
+        return opts, "hybrid n_kw (%s dense rows), mixture proposal below count %d" % (
+            max(dense_rows, 0), opts["dense_alias_min_count"])
+    if dense_alias_min_count != 0:
+        min_count = cfg.K if dense_alias_min_count < 0 else dense_alias_min_count
+        return dict(dense_rows=0, dense_alias_min_count=min_count), \
+            "dense n_kw, mixture proposal below count %d" % min_count
+    return {}, "dense n_kw"
+
+
+def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora):
+    """One more leg of the metric, timed like the headline: mean over `steps` iterations."""
+    import torch
+    from paper_1412_1576_amd import corpus, lda
+    cfg = corpus.CONFIGS[workload]
+    if workload not in corpora:
+        corpora[workload] = corpus.make_corpus(cfg)
+    doff, words = corpora[workload]
+    N = int(doff[-1])
+    opts, store = store_options(workload, cfg, words, dense_alias_min_count)
+    stream = torch.cuda.Stream()
+    g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
+                stream=stream.cuda_stream, **opts)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for it in range(warmup + steps):
+        e = ev[it - warmup] if it >= warmup else None
+        if e:
+            e[0].record(stream)
+        g.build_alias()
+        if e:
+            e[1].record(stream)
+        g.sweep(mh_steps)
+        if e:
+            e[2].record(stream)
+        g.rebuild_counts()
+        if e:
+            e[3].record(stream)
+    g.sync()
+    torch.cuda.synchronize()
+    assert int(g.get_nk().sum()) == N, "count invariant violated"
+    g.close()
+    mean = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in ev) / steps
+    step_ms, sweep_ms = mean(0, 3), mean(1, 2)
+    return {
+        "workload": "%s: N=%d tokens, V=%d, K=%d, mh_steps=%d, %s" % (cfg.name, N, cfg.V, cfg.K,
+                                                                      mh_steps, store),
+        "steps": steps, "warmup": warmup,
+        "ms_per_step": step_ms, "tokens_per_s": N / (step_ms * 1e-3),
+        "alias_ms": mean(0, 1), "sweep_ms": sweep_ms, "rebuild_ms": mean(2, 3),
+        "sweep_tokens_per_s": N / (sweep_ms * 1e-3),
+        "sweep_achieved_GBs": algorithmic_bytes_per_token(mh_steps) * N / (sweep_ms * 1e-3) / 1e9,
+        "sweep_frac_of_hbm_peak": algorithmic_bytes_per_token(mh_steps) * N / (sweep_ms * 1e-3) / 1e9
+                                  / HBM_PEAK_GBS,
     }
 
 
@@ -90,6 +163,9 @@ def main():
     ap.add_argument("--docs", type=int, default=0, help="use only the first DOCS documents' worth "
                     "of the workload (debugging; the result is then not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-legs", action="store_true", help="skip the other legs of the "
+                    "metric (c2, c4, c3 at 4 steps, c3 with a dense table for every word) that a "
+                    "default run times after the headline workload")
     ap.add_argument("--cpu-sample-docs", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true", help="also launch a plain "
                     "elementwise kernel that reads 1 GiB and writes 1 GiB (scale for HBM counters)")
@@ -121,25 +197,7 @@ def main():
     t_gen = time.perf_counter() - t0
     N = int(doff[-1])
 
-    # hybrid store (c4: dense rows for the head words; c5: no dense row): every word without a
-    # dense row draws from the mixture
-    hybrid = {}
-    store = "dense n_kw"
-    if args.workload in ("c4", "c5"):
-        dense_rows = cfg.dense_rows if args.workload == "c4" else -1
-        cnt = np.bincount(words, minlength=cfg.V)
-        tail = cnt[max(dense_rows, 0):]
-        # dense K-bin tables only for words with at least K tokens (rows that can be dense)
-        hybrid = dict(dense_rows=dense_rows,
-                      dense_alias_min_count=max(int(tail.max()) + 1, cfg.K))
-        store = "hybrid n_kw (%s dense rows), mixture proposal below count %d" % (
-            max(dense_rows, 0), hybrid["dense_alias_min_count"])
-        del cnt, tail
-        args.no_cpu_baseline = True  # the oracle keeps a dense V x K table
-    elif args.dense_alias_min_count != 0:
-        min_count = cfg.K if args.dense_alias_min_count < 0 else args.dense_alias_min_count
-        hybrid = dict(dense_rows=0, dense_alias_min_count=min_count)
-        store = "dense n_kw, mixture proposal below count %d" % min_count
+    hybrid, store = store_options(args.workload, cfg, words, args.dense_alias_min_count)
 
     stream = torch.cuda.Stream()
     t0 = time.perf_counter()
@@ -256,10 +314,20 @@ def main():
     g.close()
     if args.calibrate_copy:
         out["config"]["streaming_copy_GBs"] = copy_gbs
+    if not args.no_other_legs and not args.docs:
+        # the other K of the metric and the other forms of the headline workload, timed in the
+        # same run: (workload, mh_steps, dense_alias_min_count)
+        corpora = {args.workload: (doff, words)}
+        legs = [("c2", 2, -1), ("c3", 4, -1), ("c3", 2, 0), ("c4", 2, -1)]
+        out["config"]["other_legs"] = [
+            run_leg(w, m, max(3, min(args.steps, 10)), 1, dm, corpora)
+            for (w, m, dm) in legs if (w, m, dm) != (args.workload, args.mh_steps, args.dense_alias_min_count)]
+        corpora.clear()
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample_docs or {"c1": 1000, "c2": 60000, "c3": 600000}[args.workload]
+        sample = args.cpu_sample_docs or CPU_SAMPLE_DOCS[args.workload]
         out["cpu_baseline"] = cpu_baseline(cfg, doff, words, args.mh_steps, sample,
-                                           hybrid.get("dense_alias_min_count", 0))
+                                           hybrid.get("dense_alias_min_count", 0),
+                                           lazy_rows=args.workload in ("c4", "c5"))
     print(json.dumps(out))
 
 
