@@ -150,6 +150,18 @@ int lda_sweep_pass_ms(lda_ctx* ctx, float* word_pass_ms, float* doc_pass_ms);
 int lda_rebuild_counts(lda_ctx* ctx);
 
 /*
+ * lda_update_counts -- the counts after a sweep by the paper's own rule (Sec. 3, text after
+ * Eq. 1; applied late as in Sec. 6, "Multi-thread Efficiency"): for every token the last
+ * lda_sweep moved from topic a to topic b, n_kw[w][a] and n_k[a] lose one, n_kw[w][b] and
+ * n_k[b] gain one.  Same tables as lda_rebuild_counts, bit for bit; cheaper when few tokens
+ * move (late in training), dearer when most do.  Needs the state SWEPT reached by lda_sweep
+ * (not by lda_set_z: LDA_ERR_STATE) and the all-dense store with dense tables for every word
+ * (LDA_ERR_UNSUPPORTED otherwise: lists and hash rows are only made by the recount).
+ * SWEPT -> COUNTS_VALID.
+ */
+int lda_update_counts(lda_ctx* ctx);
+
+/*
  * lda_loglik -- log p(w, z | alpha, beta) of the collapsed model, the metric of
  * Sec. 7 ("doc-likelihood" + "word-likelihood"); fp64.  Needs valid counts.
  * doc_part / word_part may be NULL.  Synchronises.

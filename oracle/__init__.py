@@ -62,6 +62,7 @@ def bind(path):
         "ldaref_sweep": (C.c_int, [vp, C.c_int32]),
         "ldaref_sweep_tokens": (C.c_int, [vp, C.c_uint32, C.c_int32, C.c_int64, _i64p, _i32p]),
         "ldaref_rebuild_counts": (C.c_int, [vp]),
+        "ldaref_update_counts": (C.c_int, [vp]),
         "ldaref_loglik": (C.c_int, [vp] + [C.POINTER(C.c_double)] * 3),
         "ldaref_num_tokens": (C.c_int64, [vp]),
         "ldaref_sweep_index": (C.c_uint32, [vp]),
@@ -195,6 +196,9 @@ class Oracle:
 
     def rebuild_counts(self):
         _ck(lib().ldaref_rebuild_counts(self._h), "ldaref_rebuild_counts")
+
+    def update_counts(self):
+        _ck(lib().ldaref_update_counts(self._h), "ldaref_update_counts")
 
     def loglik(self):
         t, d, w = C.c_double(), C.c_double(), C.c_double()

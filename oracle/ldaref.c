@@ -308,6 +308,7 @@ typedef struct ldaref_ctx {
     uint64_t QB;
     int beta_table_built;
     int state;
+    int prev_valid;                /* znew holds the assignment before the last sweep */
     uint32_t sweep_index;
 } ldaref_ctx;
 
@@ -631,6 +632,7 @@ int ldaref_sweep(ldaref_ctx* c, int32_t mh_steps)
     int32_t* tmp = c->z; c->z = c->znew; c->znew = tmp;
     c->sweep_index += 1;
     c->state = ST_SWEPT;
+    c->prev_valid = 1;
     return LDAREF_OK;
 }
 
@@ -667,6 +669,36 @@ int ldaref_rebuild_counts(ldaref_ctx* c)
     if (!c) return LDAREF_ERR_ARG;
     count_all(c);
     c->state = ST_COUNTS_VALID;
+    c->prev_valid = 0;
+    return LDAREF_OK;
+}
+
+/* The paper's own way to keep the counts (Sec. 3, text after Eq. 1): when a token moves from
+ * topic a to topic b, n_kw[w][a], n_k[a] lose one and n_kw[w][b], n_k[b] gain one (n_kd is
+ * formed per document from z here).  Applied after a sweep for every token that moved, from
+ * the assignment before the sweep, it must leave the same tables as a recount. */
+int ldaref_update_counts(ldaref_ctx* c)
+{
+    if (!c) return LDAREF_ERR_ARG;
+    if (c->state != ST_SWEPT || !c->prev_valid) return LDAREF_ERR_STATE;
+    for (int64_t g = 0; g < c->N; ++g) {
+        const int32_t a = c->znew[g], b = c->z[g]; /* before, after */
+        if (a == b) continue;
+        if (!c->lazy_rows) {
+            c->nkw_row[c->word[g]][a] -= 1;
+            c->nkw_row[c->word[g]][b] += 1;
+        }
+        c->nk[a] -= 1;
+        c->nk[b] += 1;
+    }
+    if (c->lazy_rows) { /* rows are recounted when next needed */
+        for (int32_t w = 0; w < c->V; ++w) {
+            free(c->nkw_row[w]);
+            c->nkw_row[w] = NULL;
+        }
+    }
+    c->state = ST_COUNTS_VALID;
+    c->prev_valid = 0;
     return LDAREF_OK;
 }
 
@@ -766,6 +798,7 @@ int ldaref_set_z(ldaref_ctx* c, const int32_t* z, int64_t next_sweep_index)
     memcpy(c->z, z, sizeof(int32_t) * (size_t)c->N);
     c->sweep_index = (uint32_t)next_sweep_index;
     c->state = ST_SWEPT; /* counts are stale until rebuilt */
+    c->prev_valid = 0;
     return LDAREF_OK;
 }
 

@@ -588,6 +588,7 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
     std::swap(c->d_z, c->d_znew);
     c->sweep_index += 1;
     c->state = SWEPT;
+    c->prev_valid = true;
     return LDA_OK;
 }
 
@@ -607,6 +608,22 @@ int lda_rebuild_counts(lda_ctx* c)
 {
     if (!c) return LDA_ERR_ARG;
     const int rc = c->hybrid ? launch_rebuild_hybrid(c) : launch_rebuild(c);
+    if (rc == LDA_OK) c->state = COUNTS_VALID;
+    c->prev_valid = false;
+    return rc;
+}
+
+int lda_update_counts(lda_ctx* c)
+{
+    if (!c) return LDA_ERR_ARG;
+    if (c->hybrid)
+        return fail(c, LDA_ERR_UNSUPPORTED,
+                    "lda_update_counts: needs the all-dense store with dense tables (lists and hash "
+                    "rows are only made by lda_rebuild_counts)");
+    if (c->state != SWEPT || !c->prev_valid)
+        return fail(c, LDA_ERR_STATE, "lda_update_counts: needs the state left by lda_sweep");
+    const int rc = launch_update_counts(c);
+    c->prev_valid = false;
     if (rc == LDA_OK) c->state = COUNTS_VALID;
     return rc;
 }
@@ -655,6 +672,7 @@ int lda_set_z(lda_ctx* c, const int32_t* z, int64_t next_sweep_index)
     std::swap(c->d_z, c->d_znew);
     c->zt_current = false;
     c->td_valid = false;
+    c->prev_valid = false;
     c->sweep_index = (uint32_t)next_sweep_index;
     c->state = SWEPT;
     return LDA_OK;

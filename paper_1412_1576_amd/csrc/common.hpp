@@ -53,6 +53,7 @@ struct lda_ctx {
     hipStream_t stream = nullptr;
     int state = 0;
     uint32_t sweep_index = 0;
+    bool prev_valid = false;  // d_znew holds the assignment before the last sweep
     std::string err;
 
     // corpus, document-major (CSR order)
@@ -291,6 +292,7 @@ int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sweep_split(lda_ctx* c, int32_t mh_steps);
 int launch_tokdoc(lda_ctx* c);                               // per-token document index in its tile
 int launch_rebuild(lda_ctx* c);
+int launch_update_counts(lda_ctx* c);  // n_kw, n_k by +-1 for the tokens the last sweep moved
 int setup_sparse_rows(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sparse_rows(lda_ctx* c);   // lists, list lengths and hash rows of the sparse-row words
 int launch_nk_by_ranges(lda_ctx* c);  // n_k when K is too large for a few LDS histograms over z

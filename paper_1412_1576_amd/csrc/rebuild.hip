@@ -8,6 +8,8 @@
 // pre-zeroed row with integer atomics (order-free, hence exact).
 // n_k: an LDS-privatised histogram of z over all tokens (for very large K over a copy of z
 // partitioned by topic range, sparse_rows.hip).
+#include <algorithm>
+
 #include "common.hpp"
 #include "xcd.hpp"
 
@@ -197,7 +199,58 @@ __global__ __launch_bounds__(1024) void nk_hist_ranges_kernel(const int32_t* __r
     }
 }
 
+// The paper's incremental rule (Sec. 3): a token that moved from topic a to topic b takes one
+// from n_kw[w][a], n_k[a] and gives one to n_kw[w][b], n_k[b].  Integer atomics, so the result
+// equals the recount whatever the order.  The deltas of n_k are summed per workgroup in LDS
+// first (the all-dense store has K <= max_alias_topics()).
+__global__ __launch_bounds__(1024) void update_counts_kernel(const int32_t* __restrict__ z,
+                                                            const int32_t* __restrict__ zprev,
+                                                            const int32_t* __restrict__ word,
+                                                            int64_t N, int32_t K,
+                                                            int32_t* __restrict__ nkw,
+                                                            int32_t* __restrict__ nk)
+{
+    extern __shared__ int32_t dk[];
+    const int tid = threadIdx.x, nt = blockDim.x;
+    for (int32_t k = tid; k < K; k += nt) dk[k] = 0;
+    __syncthreads();
+    const int64_t per = (N + gridDim.x - 1) / gridDim.x;
+    const int64_t b = (int64_t)blockIdx.x * per;
+    const int64_t e = (b + per < N) ? b + per : N;
+    for (int64_t g = b + tid; g < e; g += nt) {
+        const int32_t to = __builtin_nontemporal_load(&z[g]);
+        const int32_t from = __builtin_nontemporal_load(&zprev[g]);
+        if (to == from) continue;
+        int32_t* __restrict__ row = nkw + (size_t)word[g] * (size_t)K;
+        atomicSub(&row[from], 1);
+        atomicAdd(&row[to], 1);
+        atomicSub(&dk[from], 1);
+        atomicAdd(&dk[to], 1);
+    }
+    __syncthreads();
+    for (int32_t k = tid; k < K; k += nt) {
+        const int32_t v = dk[k];
+        if (v) atomicAdd(&nk[k], v);
+    }
+}
+
 }  // namespace
+
+int launch_update_counts(lda_ctx* c)
+{
+    if (c->K > kNkRangeTopics)
+        return fail(c, LDA_ERR_UNSUPPORTED, "lda_update_counts supports K <= %d", kNkRangeTopics);
+    int64_t blocks = (c->N + 65535) / 65536;
+    blocks = std::max<int64_t>(1, std::min<int64_t>(blocks, 2048));
+    const size_t lds = sizeof(int32_t) * (size_t)c->K;
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(update_counts_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(update_counts_kernel, dim3((unsigned)blocks), dim3(1024), lds, c->stream, c->d_z,
+                       c->d_znew, c->d_word, c->N, c->K, c->d_nkw, c->d_nk);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
 
 int max_rebuild_topics() { return 36 * 1024; }
 

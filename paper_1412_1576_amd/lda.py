@@ -23,7 +23,7 @@ LDA_ERR_UNSUPPORTED = -5
 
 EXPORTS = [
     "lda_init", "lda_build_alias", "lda_sweep", "lda_sweep_pass_ms", "lda_rebuild_counts",
-    "lda_loglik", "lda_loglik_noalloc",
+    "lda_update_counts", "lda_loglik", "lda_loglik_noalloc",
     "lda_num_tokens", "lda_sweep_index", "lda_get_z", "lda_set_z", "lda_get_nk",
     "lda_get_nkw_row", "lda_get_ndk_row", "lda_get_alias_row", "lda_get_sparse_table",
     "lda_get_beta_table", "lda_sync", "lda_last_error", "lda_destroy",
@@ -87,6 +87,7 @@ def load_library():
         "lda_sweep": (C.c_int, [vp, C.c_int32]),
         "lda_sweep_pass_ms": (C.c_int, [vp, C.POINTER(C.c_float), C.POINTER(C.c_float)]),
         "lda_rebuild_counts": (C.c_int, [vp]),
+        "lda_update_counts": (C.c_int, [vp]),
         "lda_loglik": (C.c_int, [vp, dp, dp, dp]),
         "lda_loglik_noalloc": (C.c_int, [vp, dp, dp, dp]),
         "lda_num_tokens": (C.c_int64, [vp]),
@@ -181,6 +182,9 @@ class Lda:
 
     def rebuild_counts(self):
         self._ck(_lib.lda_rebuild_counts(self._h))
+
+    def update_counts(self):
+        self._ck(_lib.lda_update_counts(self._h))
 
     def loglik(self):
         t, d, w = C.c_double(), C.c_double(), C.c_double()

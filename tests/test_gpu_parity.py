@@ -322,6 +322,52 @@ def test_chain_shape_changes_between_sweeps(lda_mod, oracle_mod):
         g.close(); o.close()
 
 
+def test_incremental_count_update(lda_mod, oracle_mod):
+    """lda_update_counts (the paper's +-1 rule) against the oracle's recount and against
+    lda_rebuild_counts, over sweeps of several chain shapes (two-pass and fused), K below and
+    above 48 KB of LDS-summed n_k deltas; its state rules."""
+    for K, D in ((50, 500), (12288, 300)):
+        cfg = corpus.scaled(corpus.CONFIGS["c1"], D=D, K=K, V=900)
+        doff, words = corpus.make_corpus(cfg)
+        g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=5)
+        h = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=5)
+        o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=5)
+        for it, m in enumerate((2, 4, 1, 5, 2)):
+            for x in (g, h, o):
+                x.build_alias()
+                x.sweep(m)
+            g.update_counts()
+            h.rebuild_counts()
+            o.rebuild_counts()
+            assert np.array_equal(g.get_z(), o.get_z()), (K, it)
+            assert np.array_equal(g.get_nk(), o.get_nk()) and np.array_equal(h.get_nk(), o.get_nk()), (K, it)
+            for w in range(0, cfg.V, 7):
+                row = o.get_nkw_row(w)
+                assert np.array_equal(g.get_nkw_row(w), row) and np.array_equal(h.get_nkw_row(w), row), (K, it, w)
+            assert g.loglik() == h.loglik()
+        with pytest.raises(lda_mod.LdaError) as e:   # counts are valid: nothing to apply
+            g.update_counts()
+        assert e.value.code == lda_mod.LDA_ERR_STATE
+        g.build_alias(); g.sweep(2)
+        g.set_z(g.get_z(), 3)                        # the previous assignment is gone
+        with pytest.raises(lda_mod.LdaError) as e:
+            g.update_counts()
+        assert e.value.code == lda_mod.LDA_ERR_STATE
+        g.rebuild_counts()
+        assert np.array_equal(g.get_nk(), np.bincount(g.get_z(), minlength=cfg.K))
+        for x in (g, h, o):
+            x.close()
+    # the hybrid store keeps lists and hash rows that only the recount makes
+    cfg = corpus.scaled(corpus.CONFIGS["c1"], D=100)
+    doff, words = corpus.make_corpus(cfg)
+    g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, dense_alias_min_count=cfg.K)
+    g.build_alias(); g.sweep(2)
+    with pytest.raises(lda_mod.LdaError) as e:
+        g.update_counts()
+    assert e.value.code == lda_mod.LDA_ERR_UNSUPPORTED
+    g.close()
+
+
 def test_sweep_pass_times(lda_mod):
     cfg = corpus.scaled(corpus.CONFIGS["c1"], D=200)
     doff, words = corpus.make_corpus(cfg)

@@ -128,3 +128,29 @@ def test_checkpoint_roundtrip(oracle_mod):
     for it in range(2):
         b.build_alias(); b.sweep(2); b.rebuild_counts()
     assert a.get_z().tolist() == b.get_z().tolist()
+
+
+def test_incremental_update_equals_recount(oracle_mod):
+    """The paper's +-1 rule (Sec. 3) applied after a sweep leaves the tables of a recount."""
+    cfg, doff, words = small_corpus()
+    for lazy_rows in (False, True):
+        a = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=2, lazy_rows=lazy_rows)
+        for it in range(4):
+            a.build_alias()
+            a.sweep(2 + it % 2)
+            a.update_counts()
+            z = a.get_z()
+            ndk, nkw, nk = recount(z, doff, words, cfg.V, cfg.K)
+            assert a.get_nk().tolist() == nk.tolist(), it
+            for w in range(cfg.V):
+                assert a.get_nkw_row(w).tolist() == nkw[w].tolist(), (it, w)
+        # only right after a sweep: not twice, not after set_z
+        import pytest
+        a.build_alias(); a.sweep(2); a.update_counts()
+        with pytest.raises(oracle_mod.OracleError):
+            a.update_counts()
+        a.set_z(a.get_z(), 9)
+        with pytest.raises(oracle_mod.OracleError):
+            a.update_counts()
+        a.rebuild_counts()
+        a.close()

@@ -36,6 +36,7 @@ def pins_counts(mod):
     t_counts.test_counts_invariants_and_recount(mod)
     t_counts.test_initial_assignment_rule(mod)
     t_counts.test_loglik_matches_scipy(mod)
+    t_counts.test_incremental_update_equals_recount(mod)
 
 
 def pins_philox(mod):
@@ -69,6 +70,8 @@ MUTANTS = [
      pins_philox),
     ("n_k not counted per token", "        c->nk[c->z[g]] += 1;\n", "        c->nk[c->z[g]] = 1;\n",
      pins_counts),
+    ("incremental update moves the count the wrong way", "        c->nk[a] -= 1;\n",
+     "        c->nk[a] += 1;\n", pins_counts),
     ("initial topic from the wrong counter", "token_random(seed, (uint64_t)g, 0xFFFFFFFFu, 0u, x);",
      "token_random(seed, (uint64_t)g, 0u, 0u, x);", pins_counts),
     ("log-likelihood misses lgamma(alpha)", "kadd(&sd, lgamma((double)ndk[k] + c->alpha) - lga);",
