@@ -89,7 +89,15 @@ typedef struct lda_options {
                                       (2^22 when every n_kw row is dense and the corpus has at
                                       least 2^28 tokens, else one bucket);
                                       -1: one bucket (plain word order) */
-    int32_t reserved[7];           /* must be zero */
+    int32_t doc_refresh;           /* 1: lda_sweep refreshes the doc side after every token (Sec. 4.2,
+                                      footnote 4): the tokens of a document are visited in order
+                                      and each sees, in n_kd and in the doc-proposal's draw, the
+                                      topics its predecessors of the same sweep were just given;
+                                      the word side stays at the snapshot (Sec. 6).  All-dense
+                                      store with dense tables, documents of at most 4096 tokens,
+                                      at most 4 steps (LDA_ERR_UNSUPPORTED otherwise).  0: every
+                                      token reads the snapshot (the default, and the fast path) */
+    int32_t reserved[6];           /* must be zero */
 } lda_options;
 
 /*

@@ -61,6 +61,9 @@ def bind(path):
         "ldaref_build_alias": (C.c_int, [vp]),
         "ldaref_sweep": (C.c_int, [vp, C.c_int32]),
         "ldaref_sweep_tokens": (C.c_int, [vp, C.c_uint32, C.c_int32, C.c_int64, _i64p, _i32p]),
+        "ldaref_sweep_doc_refresh": (C.c_int, [vp, C.c_int32]),
+        "ldaref_chain_with_doc": (C.c_int, [vp, C.c_int64, C.c_uint32, C.c_int32, C.c_int32, _i32p,
+                                            C.POINTER(C.c_int32)]),
         "ldaref_rebuild_counts": (C.c_int, [vp]),
         "ldaref_update_counts": (C.c_int, [vp]),
         "ldaref_loglik": (C.c_int, [vp] + [C.POINTER(C.c_double)] * 3),
@@ -193,6 +196,16 @@ class Oracle:
         _ck(lib().ldaref_sweep_tokens(self._h, int(sweep_index), mh_steps, len(token_ids),
                                       token_ids, out), "ldaref_sweep_tokens")
         return out
+
+    def sweep_doc_refresh(self, mh_steps):
+        _ck(lib().ldaref_sweep_doc_refresh(self._h, mh_steps), "ldaref_sweep_doc_refresh")
+
+    def chain_with_doc(self, g, sweep_index, mh_steps, zdoc):
+        zdoc = np.ascontiguousarray(zdoc, np.int32)
+        out = C.c_int32()
+        _ck(lib().ldaref_chain_with_doc(self._h, int(g), int(sweep_index), mh_steps, len(zdoc), zdoc,
+                                        C.byref(out)), "ldaref_chain_with_doc")
+        return out.value
 
     def rebuild_counts(self):
         _ck(lib().ldaref_rebuild_counts(self._h), "ldaref_rebuild_counts")

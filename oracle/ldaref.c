@@ -636,6 +636,78 @@ int ldaref_sweep(ldaref_ctx* c, int32_t mh_steps)
     return LDAREF_OK;
 }
 
+/* Sweep with the doc side refreshed after every token (Sec. 4.2, footnote 4: the doc-proposal
+ * "changes after every token to reflect the current state" of the document's assignments)
+ * while the word side -- n_kw, n_k and the word-proposal tables -- stays at the snapshot
+ * (Sec. 6, the immutable model slice).  The tokens of a document are visited in order; token
+ * i sees the topics that tokens < i of the same document were just given, in n_kd and in the
+ * doc-proposal's draw.  Its own entry is still its snapshot topic z0, which is what the "-di"
+ * exclusion removes from all three tables.  Documents stay independent of each other. */
+int ldaref_sweep_doc_refresh(ldaref_ctx* c, int32_t mh_steps)
+{
+    if (!c || mh_steps < 1) return LDAREF_ERR_ARG;
+    if (c->state != ST_ALIAS_VALID) return LDAREF_ERR_STATE;
+    int32_t* ndk = c->doc_scratch;
+    int32_t maxL = 0;
+    for (int64_t d = 0; d < c->D; ++d)
+        if (c->doff[d + 1] - c->doff[d] > maxL) maxL = (int32_t)(c->doff[d + 1] - c->doff[d]);
+    int32_t* zcur = (int32_t*)malloc(sizeof(int32_t) * (size_t)(maxL > 0 ? maxL : 1));
+    if (!zcur) return LDAREF_ERR_OOM;
+    for (int64_t d = 0; d < c->D; ++d) {
+        const int64_t b = c->doff[d], e = c->doff[d + 1];
+        const int32_t L = (int32_t)(e - b);
+        int rc = LDAREF_OK;
+        for (int64_t g = b; g < e; ++g) {
+            zcur[g - b] = c->z[g];
+            ndk[c->z[g]] += 1;
+        }
+        for (int64_t g = b; g < e && rc == LDAREF_OK; ++g) {
+            int32_t s;
+            rc = token_chain(c, g, c->word[g], ndk, zcur, L, c->sweep_index, mh_steps, &s);
+            if (rc == LDAREF_OK) {
+                ndk[zcur[g - b]] -= 1;
+                ndk[s] += 1;
+                zcur[g - b] = s;
+                c->znew[g] = s;
+            }
+        }
+        for (int32_t i = 0; i < L; ++i) ndk[zcur[i]] = 0;
+        for (int64_t g = b; g < e; ++g) ndk[c->z[g]] = 0;
+        if (rc) { free(zcur); return rc; }
+    }
+    free(zcur);
+    int32_t* tmp = c->z; c->z = c->znew; c->znew = tmp;
+    c->sweep_index += 1;
+    c->state = ST_SWEPT;
+    c->prev_valid = 1;
+    return LDAREF_OK;
+}
+
+/* One token's chain with the document side taken from a caller-given assignment zdoc[0..L)
+ * of its document (zdoc at the token's own place must be its snapshot topic); the word side
+ * is the snapshot.  Does not change the context. */
+int ldaref_chain_with_doc(ldaref_ctx* c, int64_t g, uint32_t sweep_index, int32_t mh_steps,
+                          int32_t L, const int32_t* zdoc, int32_t* out)
+{
+    if (!c || mh_steps < 1 || !zdoc || !out || g < 0 || g >= c->N) return LDAREF_ERR_ARG;
+    if (c->state != ST_ALIAS_VALID) return LDAREF_ERR_STATE;
+    int64_t lo = 0, hi = c->D;
+    while (hi - lo > 1) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (c->doff[mid] <= g) lo = mid; else hi = mid;
+    }
+    while (c->doff[lo + 1] <= g) ++lo;
+    if (L != (int32_t)(c->doff[lo + 1] - c->doff[lo]) || zdoc[g - c->doff[lo]] != c->z[g])
+        return LDAREF_ERR_ARG;
+    for (int32_t i = 0; i < L; ++i)
+        if (zdoc[i] < 0 || zdoc[i] >= c->K) return LDAREF_ERR_ARG;
+    int32_t* ndk = c->doc_scratch;
+    for (int32_t i = 0; i < L; ++i) ndk[zdoc[i]] += 1;
+    int rc = token_chain(c, g, c->word[g], ndk, zdoc, L, sweep_index, mh_steps, out);
+    for (int32_t i = 0; i < L; ++i) ndk[zdoc[i]] = 0;
+    return rc;
+}
+
 /* Chains of selected tokens only, against the current snapshot, for an
  * arbitrary sweep index; does not change the context's assignment. */
 int ldaref_sweep_tokens(ldaref_ctx* c, uint32_t sweep_index, int32_t mh_steps, int64_t n,

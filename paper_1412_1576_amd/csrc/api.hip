@@ -346,7 +346,9 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         o.sweep_block_threads < 0 || o.rebuild_tile_tokens < 0 || o.time_sweep_passes < 0 ||
         o.time_sweep_passes > 1)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
-    for (int i = 0; i < 7; ++i)
+    if (o.doc_refresh < 0 || o.doc_refresh > 1)
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: doc_refresh must be 0 or 1");
+    for (int i = 0; i < 6; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
     if (o.record_bucket_tokens < -1 ||
         (o.record_bucket_tokens > 0 && (o.record_bucket_tokens & (o.record_bucket_tokens - 1)) != 0))
@@ -418,6 +420,11 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         return bail(fail(nullptr, LDA_ERR_OOM, "lda_init: host allocation failed"));
     }
     for (int64_t d = 0; d <= D; ++d) c->h_doff[d] = (int32_t)doc_offsets[d];
+    for (int64_t d = 0; d < D; ++d) c->longest_doc = std::max(c->longest_doc, c->h_doff[d + 1] - c->h_doff[d]);
+    if (o.doc_refresh && (hybrid || c->longest_doc > refresh_sweep_max_doc()))
+        return bail(fail(nullptr, LDA_ERR_UNSUPPORTED,
+                         "lda_init: doc_refresh needs the all-dense store with dense tables and "
+                         "documents of at most %d tokens", refresh_sweep_max_doc()));
 
     std::vector<int32_t> chunk_doc;
     std::vector<int64_t> long_slot;
@@ -576,7 +583,12 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
         return fail(c, LDA_ERR_STATE, "lda_sweep: needs fresh alias tables (call lda_build_alias)");
     if (c->sweep_index == 0xFFFFFFFEu) return fail(c, LDA_ERR_STATE, "lda_sweep: sweep index exhausted");
     int rc;
-    if (split_sweep_supported(c, mh_steps)) {
+    if (c->opt.doc_refresh) {
+        rc = launch_sweep_doc_refresh(c, mh_steps, c->longest_doc);
+        c->zt_current = false;  // only the doc-major assignment is written
+        c->td_valid = false;
+        c->pass_ev_recorded = false;
+    } else if (split_sweep_supported(c, mh_steps)) {
         rc = launch_sweep_split(c, mh_steps);
     } else {
         rc = c->hybrid ? launch_sweep_hybrid(c, mh_steps) : launch_sweep(c, mh_steps);

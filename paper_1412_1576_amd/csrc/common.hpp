@@ -54,6 +54,7 @@ struct lda_ctx {
     int state = 0;
     uint32_t sweep_index = 0;
     bool prev_valid = false;  // d_znew holds the assignment before the last sweep
+    int32_t longest_doc = 0;  // tokens of the longest document
     std::string err;
 
     // corpus, document-major (CSR order)
@@ -286,6 +287,9 @@ __host__ __device__ inline void unpack_mix_bin(const uint4& e, bool own, int32_t
     count = (int32_t)((sel >> kMixTopicBits) | (hi << 12));
 }
 int launch_sweep(lda_ctx* c, int32_t mh_steps);
+// Sweep with the doc side refreshed after every token (sweep_refresh.hip)
+int refresh_sweep_max_doc();
+int launch_sweep_doc_refresh(lda_ctx* c, int32_t mh_steps, int32_t longest_doc);
 // Two-pass sweep (word pass over word-major tokens, doc pass over document tiles)
 bool split_sweep_supported(const lda_ctx* c, int32_t mh_steps);
 int setup_split_sweep(lda_ctx* c, const std::vector<int32_t>& woff);

@@ -11,6 +11,7 @@ import test_oracle_alias as t_alias
 import test_oracle_counts_loglik as t_counts
 import test_oracle_mh as t_mh
 import test_oracle_philox as t_philox
+import test_oracle_doc_refresh as t_refresh
 
 SRC = os.path.join(os.path.dirname(oracle.__file__), "ldaref.c")
 
@@ -37,6 +38,10 @@ def pins_counts(mod):
     t_counts.test_initial_assignment_rule(mod)
     t_counts.test_loglik_matches_scipy(mod)
     t_counts.test_incremental_update_equals_recount(mod)
+
+
+def pins_refresh(mod):
+    t_refresh.test_sweep_is_the_fold_of_chains_in_token_order(mod)
 
 
 def pins_philox(mod):
@@ -72,6 +77,7 @@ MUTANTS = [
      pins_counts),
     ("incremental update moves the count the wrong way", "        c->nk[a] -= 1;\n",
      "        c->nk[a] += 1;\n", pins_counts),
+    ("doc side not refreshed after a token", "                zcur[g - b] = s;\n", "", pins_refresh),
     ("initial topic from the wrong counter", "token_random(seed, (uint64_t)g, 0xFFFFFFFFu, 0u, x);",
      "token_random(seed, (uint64_t)g, 0u, 0u, x);", pins_counts),
     ("log-likelihood misses lgamma(alpha)", "kadd(&sd, lgamma((double)ndk[k] + c->alpha) - lga);",
@@ -113,5 +119,5 @@ def test_mutant_is_caught(name, old, new, pins, swap_lib, tmp_path):
 
 def test_pins_pass_on_the_real_oracle(swap_lib):
     oracle._lib = oracle.bind(oracle.build_oracle())
-    for pins in (pins_mh, pins_alias, pins_counts, pins_philox):
+    for pins in (pins_mh, pins_alias, pins_counts, pins_philox, pins_refresh):
         pins(oracle)
