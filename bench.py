@@ -107,8 +107,9 @@ def store_options(workload, cfg, words, dense_alias_min_count):
     return {}, "dense n_kw"
 
 
-def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora):
-    """One more leg of the metric, timed like the headline: mean over `steps` iterations."""
+def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora, stream_block_tokens=0):
+    """One more leg of the metric, timed like the headline: mean over `steps` iterations.
+    stream_block_tokens > 0: the corpus streamed from pinned host memory in blocks."""
     import torch
     from paper_1412_1576_amd import corpus, lda
     cfg = corpus.CONFIGS[workload]
@@ -119,7 +120,7 @@ def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora):
     opts, store = store_options(workload, cfg, words, dense_alias_min_count)
     stream = torch.cuda.Stream()
     g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                stream=stream.cuda_stream, **opts)
+                stream=stream.cuda_stream, stream_block_tokens=stream_block_tokens, **opts)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     for it in range(warmup + steps):
         e = ev[it - warmup] if it >= warmup else None
@@ -140,6 +141,8 @@ def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora):
     g.close()
     mean = lambda a, b: sum(e[a].elapsed_time(e[b]) for e in ev) / steps
     step_ms, sweep_ms = mean(0, 3), mean(1, 2)
+    if stream_block_tokens:
+        store += "; streamed from pinned host memory in blocks of %d tokens" % stream_block_tokens
     return {
         "workload": "%s: N=%d tokens, V=%d, K=%d, mh_steps=%d, %s" % (cfg.name, N, cfg.V, cfg.K,
                                                                       mh_steps, store),
@@ -174,6 +177,8 @@ def main():
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--record-bucket-tokens", type=int, default=0, help="order of the records the "
                     "sweep's passes exchange (lda_options.record_bucket_tokens); 0: default")
+    ap.add_argument("--stream-block-tokens", type=int, default=0, help="stream the corpus from "
+                    "pinned host memory in blocks of this many tokens (lda_options)")
     ap.add_argument("--dense-alias-min-count", type=int, default=-1, help="c1-c3: words with "
                     "fewer tokens draw from the sparsified mixture word-proposal (Sec. 4.2) "
                     "instead of a dense K-bin table; -1 (default) = K; 0 = dense tables for "
@@ -204,7 +209,8 @@ def main():
     g = lda.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                 stream=stream.cuda_stream, sweep_chunk_tokens=args.chunk_tokens,
                 sweep_block_threads=args.block_threads, rebuild_tile_tokens=args.tile_tokens,
-                time_sweep_passes=1, record_bucket_tokens=args.record_bucket_tokens, **hybrid)
+                time_sweep_passes=1, record_bucket_tokens=args.record_bucket_tokens,
+                stream_block_tokens=args.stream_block_tokens, **hybrid)
     g.sync()
     t_init = time.perf_counter() - t0
 
@@ -322,6 +328,32 @@ def main():
         out["config"]["other_legs"] = [
             run_leg(w, m, max(3, min(args.steps, 10)), 1, dm, corpora)
             for (w, m, dm) in legs if (w, m, dm) != (args.workload, args.mh_steps, args.dense_alias_min_count)]
+        # streamed data blocks: the K = 10^6 slice resident and in five blocks of 10^8 tokens from
+        # pinned host memory (13 B per token to the device, 4 B back, every sweep)
+        res = run_leg("c5", 2, 3, 1, -1, corpora)
+        stm = run_leg("c5", 2, 3, 1, -1, corpora, stream_block_tokens=100_000_000)
+        n5 = int(corpora["c5"][0][-1])
+        # what the host link alone allows: a pinned 1 GiB buffer copied to the device
+        pin = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        dev = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dev.copy_(pin, non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(4):
+            dev.copy_(pin, non_blocking=True)
+        torch.cuda.synchronize()
+        h2d_gbs = 4 * (1 << 30) / (time.perf_counter() - t0) / 1e9
+        del pin, dev
+        load_ms = 13.0 * n5 / h2d_gbs / 1e6
+        out["config"]["streamed_blocks"] = {
+            "resident": res, "streamed": stm,
+            "streamed_over_resident_sweep_time": stm["sweep_ms"] / res["sweep_ms"],
+            "streamed_over_resident_iteration_time": stm["ms_per_step"] / res["ms_per_step"],
+            "host_link_GBs_during_streamed_sweep": 17.0 * n5 / (stm["sweep_ms"] * 1e-3) / 1e9,
+            "host_to_device_GBs_plain_copy": h2d_gbs,
+            "load_alone_ms": load_ms,   # 13 B per token at the plain copy's rate
+            "overlap_efficiency": load_ms / stm["sweep_ms"],  # 1: the sweep hides behind the loads
+        }
         corpora.clear()
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_docs or CPU_SAMPLE_DOCS[args.workload]

@@ -32,7 +32,9 @@
  *     context's HIP stream and return; accessors and lda_loglik synchronise.
  *     (lda_build_alias may run part of its kernels on a second stream of the
  *     library's own, of default priority, forked from and joined to the context's
- *     stream by events: work queued after the call still sees every table.)
+ *     stream by events: work queued after the call still sees every table.  With
+ *     stream_block_tokens the copies of the blocks run on two more such streams;
+ *     lda_sync waits for them too.)
  *   - A context is not thread-safe.  Calls must follow the state machine
  *       COUNTS_VALID --lda_build_alias--> ALIAS_VALID --lda_sweep--> SWEPT
  *       SWEPT --lda_rebuild_counts--> COUNTS_VALID
@@ -97,7 +99,19 @@ typedef struct lda_options {
                                       store with dense tables, documents of at most 4096 tokens,
                                       at most 4 steps (LDA_ERR_UNSUPPORTED otherwise).  0: every
                                       token reads the snapshot (the default, and the fast path) */
-    int32_t reserved[6];           /* must be zero */
+    int32_t stream_block_tokens;   /* > 0: streamed data blocks (Sec. 3; Sec. 6, Fig. 7).  The model
+                                      stays on the device; the per-token arrays move to pinned
+                                      host memory when lda_init is done and every lda_sweep brings
+                                      them in block by block -- runs of whole documents of about
+                                      this many tokens, the next block loading while the current
+                                      one is swept -- and takes the new topics back.  4 bytes per
+                                      token stay resident (the word-major copy of z that the count
+                                      rebuild reads).  Results are those of the resident run, bit
+                                      for bit.  lda_init itself still holds the whole corpus on
+                                      the device once.  Not with doc_refresh (LDA_ERR_ARG), not
+                                      with documents longer than a sweep tile, not
+                                      lda_update_counts (LDA_ERR_UNSUPPORTED).  0: resident */
+    int32_t reserved[5];           /* must be zero */
 } lda_options;
 
 /*

@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 ROOT = os.path.dirname(HERE)
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "liblda_mi355x.so")
-SOURCES = ["api.hip", "layout.hip", "alias.hip", "sweep.hip", "sweep_split.hip", "sweep_refresh.hip", "rebuild.hip", "sparse_rows.hip", "loglik.hip"]
+SOURCES = ["api.hip", "layout.hip", "alias.hip", "sweep.hip", "sweep_split.hip", "sweep_refresh.hip", "stream_blocks.hip", "rebuild.hip", "sparse_rows.hip", "loglik.hip"]
 
 # -ffp-contract=off: the accept test and the alias quotients are defined with
 # separately rounded fp64 operations.  Packed-fp32 code generation is disabled.

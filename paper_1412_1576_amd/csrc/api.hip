@@ -348,7 +348,9 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         return fail(nullptr, LDA_ERR_ARG, "lda_init: option out of range");
     if (o.doc_refresh < 0 || o.doc_refresh > 1)
         return fail(nullptr, LDA_ERR_ARG, "lda_init: doc_refresh must be 0 or 1");
-    for (int i = 0; i < 6; ++i)
+    if (o.stream_block_tokens < 0 || (o.stream_block_tokens > 0 && o.doc_refresh))
+        return fail(nullptr, LDA_ERR_ARG, "lda_init: stream_block_tokens must be >= 0, and 0 with doc_refresh");
+    for (int i = 0; i < 5; ++i)
         if (o.reserved[i] != 0) return fail(nullptr, LDA_ERR_ARG, "lda_init: reserved option set");
     if (o.record_bucket_tokens < -1 ||
         (o.record_bucket_tokens > 0 && (o.record_bucket_tokens & (o.record_bucket_tokens - 1)) != 0))
@@ -382,6 +384,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
         // more than the word pass and the rebuild lose (measured: 7 * 10^8 tokens gain, 10^8
         // tokens and the hybrid store lose a few percent)
         if (bucket == 0) bucket = (H == V && N >= ((int64_t)1 << 28)) ? (1 << 22) : -1;
+        if (o.stream_block_tokens > 0) bucket = -1;  // the two-pass sweep's records do not exist
         c->record_bucket_shift = 0;
         if (bucket > 0 && (int64_t)bucket < N)
             while ((1 << c->record_bucket_shift) < bucket) ++c->record_bucket_shift;
@@ -434,7 +437,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     // chains of one or two steps leave room for 768-thread workgroups on tiles of 1536 tokens
     // (measured: 7 % faster doc pass at K = 10 000); longer chains need the registers
     std::vector<int32_t> chunk_doc2;
-    if (big_tiles && o.sweep_chunk_tokens == 0 && o.sweep_block_threads == 0) {
+    if (big_tiles && o.sweep_chunk_tokens == 0 && o.sweep_block_threads == 0 && o.stream_block_tokens == 0) {
         std::vector<int32_t> same_long;
         c->chunk_tokens2 = 1536;
         c->chunk_docs2 = 255;
@@ -552,6 +555,13 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
 
     TRY(hybrid ? launch_rebuild_hybrid(c) : launch_rebuild(c));
     TRY_HIP(hipStreamSynchronize(c->stream));
+    if (o.stream_block_tokens > 0) {
+        rc = enter_streamed_mode(c, chunk_doc);
+        if (rc != LDA_OK) {
+            leave_streamed_mode(c);
+            return bail(rc);
+        }
+    }
 #undef TRY
 #undef TRY_HIP
     c->state = COUNTS_VALID;
@@ -583,6 +593,16 @@ int lda_sweep(lda_ctx* c, int32_t mh_steps)
         return fail(c, LDA_ERR_STATE, "lda_sweep: needs fresh alias tables (call lda_build_alias)");
     if (c->sweep_index == 0xFFFFFFFEu) return fail(c, LDA_ERR_STATE, "lda_sweep: sweep index exhausted");
     int rc;
+    if (c->streamed) {
+        rc = launch_sweep_streamed(c, mh_steps);
+        c->pass_ev_recorded = false;
+        if (rc != LDA_OK) return rc;
+        std::swap(c->h_z, c->h_znew);
+        c->sweep_index += 1;
+        c->state = SWEPT;
+        c->prev_valid = false;
+        return LDA_OK;
+    }
     if (c->opt.doc_refresh) {
         rc = launch_sweep_doc_refresh(c, mh_steps, c->longest_doc);
         c->zt_current = false;  // only the doc-major assignment is written
@@ -628,6 +648,8 @@ int lda_rebuild_counts(lda_ctx* c)
 int lda_update_counts(lda_ctx* c)
 {
     if (!c) return LDA_ERR_ARG;
+    if (c->streamed)
+        return fail(c, LDA_ERR_UNSUPPORTED, "lda_update_counts: not with streamed data blocks");
     if (c->hybrid)
         return fail(c, LDA_ERR_UNSUPPORTED,
                     "lda_update_counts: needs the all-dense store with dense tables (lists and hash "
@@ -662,6 +684,7 @@ int lda_get_z(lda_ctx* c, int32_t* z)
 {
     if (!c) return LDA_ERR_ARG;
     if (!z) return fail(c, LDA_ERR_ARG, "lda_get_z: NULL buffer");
+    if (c->streamed) return streamed_get_z(c, z);
     LDA_HIP(c, hipMemcpyAsync(z, c->d_z, sizeof(int32_t) * (size_t)c->N, hipMemcpyDeviceToHost,
                               c->stream));
     LDA_HIP(c, hipStreamSynchronize(c->stream));
@@ -674,6 +697,15 @@ int lda_set_z(lda_ctx* c, const int32_t* z, int64_t next_sweep_index)
     if (!z) return fail(c, LDA_ERR_ARG, "lda_set_z: NULL buffer");
     if (next_sweep_index < 0 || next_sweep_index > 0xFFFFFFFELL)
         return fail(c, LDA_ERR_ARG, "lda_set_z: sweep index out of range");
+    if (c->streamed) {
+        const int rc = streamed_set_z(c, z);
+        if (rc != LDA_OK) return rc;
+        c->td_valid = false;
+        c->prev_valid = false;
+        c->sweep_index = (uint32_t)next_sweep_index;
+        c->state = SWEPT;
+        return LDA_OK;
+    }
     // stage in the spare buffer, validate, then adopt
     LDA_HIP(c, hipMemcpyAsync(c->d_znew, z, sizeof(int32_t) * (size_t)c->N, hipMemcpyHostToDevice,
                               c->stream));
@@ -821,6 +853,7 @@ int lda_get_beta_table(lda_ctx* c, uint32_t* split, uint32_t* alias, uint32_t* c
 int lda_sync(lda_ctx* c)
 {
     if (!c) return LDA_ERR_ARG;
+    if (c->streamed) return streamed_sync(c);
     LDA_HIP(c, hipStreamSynchronize(c->stream));
     return LDA_OK;
 }
@@ -834,6 +867,7 @@ void lda_destroy(lda_ctx* c)
 {
     if (!c) return;
     (void)hipStreamSynchronize(c->stream);
+    leave_streamed_mode(c);
     free_all(c);
     delete c;
 }

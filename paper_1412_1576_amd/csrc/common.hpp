@@ -41,6 +41,22 @@ struct PartTile {
     int32_t p0, p1;
 };
 
+// Streamed data blocks (stream_blocks.hip): tiles [c0, c1) = tokens [g0, g1) of the corpus
+struct StreamBlock {
+    int32_t c0, c1;
+    int64_t g0, g1;
+};
+
+// One of the two device buffers a block is loaded into
+struct BlockBuffer {
+    int32_t* word = nullptr;
+    int32_t* z = nullptr;
+    int32_t* znew = nullptr;
+    int32_t* wpos = nullptr;
+    uint8_t* tokdoc = nullptr;
+    hipEvent_t loaded = nullptr, computed = nullptr, stored = nullptr;
+};
+
 }  // namespace lda
 
 struct lda_ctx {
@@ -193,6 +209,17 @@ struct lda_ctx {
     lda::PartTile* d_nk_tiles = nullptr;
     int32_t n_nk_tiles = 0;
     uint32_t* d_nk_ranges = nullptr;
+    // streamed data blocks: the per-token arrays live in pinned host memory and pass through two
+    // device buffers; d_word, d_z, d_znew, d_gid, d_wpos, d_tokdoc are then NULL between calls
+    bool streamed = false;
+    std::vector<lda::StreamBlock> blocks;
+    int64_t max_block_tokens = 0;
+    int32_t *h_word = nullptr, *h_z = nullptr, *h_znew = nullptr, *h_wpos = nullptr;
+    uint8_t* h_tokdoc = nullptr;
+    lda::BlockBuffer buf[2];
+    hipStream_t load_stream = nullptr, store_stream = nullptr;
+    hipEvent_t pass_begin = nullptr, pass_end = nullptr, stored_all = nullptr;
+    bool stored_all_recorded = false;
     // scratch
     double* d_partial = nullptr;       // per-block partial sums (log-likelihood)
     int32_t n_partial = 0;
@@ -301,6 +328,18 @@ int setup_sparse_rows(lda_ctx* c, const std::vector<int32_t>& woff);
 int launch_sparse_rows(lda_ctx* c);   // lists, list lengths and hash rows of the sparse-row words
 int launch_nk_by_ranges(lda_ctx* c);  // n_k when K is too large for a few LDS histograms over z
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part);
+int launch_loglik_doc_tiles(lda_ctx* c, double* d_partial);  // partial[tile] of the bound tiles
+// zw[wpos[i]] = z[i], i < n: topics into the word-major copy
+int launch_scatter_word_major(lda_ctx* c, const int32_t* z, const int32_t* wpos, int64_t n);
+// streamed data blocks (stream_blocks.hip)
+int enter_streamed_mode(lda_ctx* c, const std::vector<int32_t>& chunk_doc);
+void leave_streamed_mode(lda_ctx* c);
+int launch_sweep_streamed(lda_ctx* c, int32_t mh_steps);
+int launch_loglik_doc_streamed(lda_ctx* c, double* d_partial);
+int streamed_get_z(lda_ctx* c, int32_t* z);
+int streamed_set_z(lda_ctx* c, const int32_t* z);
+int streamed_doc_z(lda_ctx* c, int64_t d, const int32_t** z_shifted);
+int streamed_sync(lda_ctx* c);
 int launch_ndk_row(lda_ctx* c, int64_t d);                  // dense n_dk row into c->d_row
 int launch_check_range(lda_ctx* c, const int32_t* d_vals, int64_t n, int32_t lo, int32_t hi,
                        bool* ok);

@@ -219,15 +219,8 @@ int run_loglik(lda_ctx* c, double* d_partial, double* h, size_t h_cap, double* d
     int rc;
 
     if (c->n_chunks > 0) {
-        const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs) +
-                           sizeof(int32_t) * 2 * (size_t)c->chunk_tokens;
-        if (lds > 48 * 1024)
-            LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(loglik_doc_tiles_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(loglik_doc_tiles_kernel, dim3(c->n_chunks), dim3(c->sweep_block), lds,
-                           c->stream, c->d_z, c->d_doff, c->d_chunk_doc, c->d_tokdoc, c->chunk_tokens,
-                           c->chunk_docs, c->alpha, c->alphabar, lga, lgab, d_partial);
-        LDA_HIP(c, hipGetLastError());
+        rc = c->streamed ? launch_loglik_doc_streamed(c, d_partial) : launch_loglik_doc_tiles(c, d_partial);
+        if (rc != LDA_OK) return rc;
         if ((rc = sum_partials(c, d_partial, (size_t)c->n_chunks, h, h_cap, &part)) != LDA_OK) return rc;
         doc += part;
     }
@@ -270,6 +263,22 @@ int run_loglik(lda_ctx* c, double* d_partial, double* h, size_t h_cap, double* d
 }
 
 }  // namespace
+
+// doc part of the tiles the context's token arrays are bound to: partial[tile]
+int launch_loglik_doc_tiles(lda_ctx* c, double* d_partial)
+{
+    const double lga = lgamma(c->alpha), lgab = lgamma(c->alphabar);
+    const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs) +
+                       sizeof(int32_t) * 2 * (size_t)c->chunk_tokens;
+    if (lds > 48 * 1024)
+        LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(loglik_doc_tiles_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(loglik_doc_tiles_kernel, dim3(c->n_chunks), dim3(c->sweep_block), lds, c->stream,
+                       c->d_z, c->d_doff, c->d_chunk_doc, c->d_tokdoc, c->chunk_tokens, c->chunk_docs,
+                       c->alpha, c->alphabar, lga, lgab, d_partial);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
 
 int launch_loglik(lda_ctx* c, double* doc_part, double* word_part)
 {

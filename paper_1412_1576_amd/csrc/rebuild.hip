@@ -261,12 +261,8 @@ int launch_dense_rows(lda_ctx* c)
 {
     const int32_t K = c->K;
     if (!c->zt_current) {  // the sweep's doc pass may have written the new assignment already
-        const int64_t per_xcd = (c->N + kXcds - 1) / kXcds;
-        const int64_t per_block = kScatterBlock * kScatterPerThread;
-        const int64_t blocks = ((per_xcd + per_block - 1) / per_block) * kXcds;
-        hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(kScatterBlock), 0, c->stream,
-                           c->d_z, c->d_wpos, c->N, c->d_zt, c->zt_shift);
-        LDA_HIP(c, hipGetLastError());
+        const int rc = launch_scatter_word_major(c, c->d_z, c->d_wpos, c->N);
+        if (rc != LDA_OK) return rc;
         c->zt_current = true;
         c->td_valid = false;  // any stored doc proposals belong to another assignment
     }
@@ -309,12 +305,24 @@ int launch_nk_hist(lda_ctx* c)
         LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(nk_hist_ranges_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     hipLaunchKernelGGL(nk_hist_ranges_kernel, dim3((unsigned)blocks, (unsigned)nr), dim3(1024), lds,
-                       c->stream, c->d_z, c->N, K, span, c->d_nk);
+                       c->stream, c->streamed ? c->d_zt : c->d_z, c->N, K, span, c->d_nk);
     LDA_HIP(c, hipGetLastError());
     return LDA_OK;
 }
 
 }  // namespace
+
+int launch_scatter_word_major(lda_ctx* c, const int32_t* z, const int32_t* wpos, int64_t n)
+{
+    if (n <= 0) return LDA_OK;
+    const int64_t per_xcd = (n + kXcds - 1) / kXcds;
+    const int64_t per_block = kScatterBlock * kScatterPerThread;
+    const int64_t blocks = ((per_xcd + per_block - 1) / per_block) * kXcds;
+    hipLaunchKernelGGL(scatter_wm_kernel, dim3((unsigned)blocks), dim3(kScatterBlock), 0, c->stream, z, wpos,
+                       n, c->d_zt, c->zt_shift);
+    LDA_HIP(c, hipGetLastError());
+    return LDA_OK;
+}
 
 int launch_rebuild(lda_ctx* c)
 {

@@ -606,7 +606,8 @@ int launch_nk_by_ranges(lda_ctx* c)
     uint32_t* cursor = dcount + nd;
     uint32_t* base = cursor + nd;      // one zero
     uint32_t* dstart = base + 1;       // nd + 1 entries
-    const TopicSource T{c->d_z, nullptr, 0, 0xFFFFFFFFu};
+    // any order of the topics will do: the word-major copy when z itself is not resident
+    const TopicSource T{c->streamed ? c->d_zt : c->d_z, nullptr, 0, 0xFFFFFFFFu};
     const PartTile* tiles = c->d_nk_tiles;
     hipLaunchKernelGGL(fill_u32_kernel, dim3(blocks_for(c->K, 256, 1024)), dim3(256), 0, c->stream,
                        reinterpret_cast<uint32_t*>(c->d_nk), (int64_t)c->K, 0u);

@@ -485,12 +485,17 @@ __global__ __launch_bounds__(1024) void ndk_row_long_kernel(const int32_t* z, co
 int launch_ndk_row(lda_ctx* c, int64_t d)
 {
     const int32_t L = c->h_doff[d + 1] - c->h_doff[d];
+    const int32_t* z = c->d_z;
+    if (c->streamed) {  // the document's topics come from the pinned copy
+        const int rc = streamed_doc_z(c, d, &z);
+        if (rc != LDA_OK) return rc;
+    }
     if (L <= c->chunk_tokens) {
         const size_t lds = doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs);
         if (lds > 48 * 1024)
             LDA_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void*>(ndk_row_tile_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(ndk_row_tile_kernel, dim3(1), dim3(256), lds, c->stream, c->d_z,
+        hipLaunchKernelGGL(ndk_row_tile_kernel, dim3(1), dim3(256), lds, c->stream, z,
                            c->d_doff, (int32_t)d, c->chunk_tokens, c->K, c->d_row);
     } else {
         // the d-th long document's workspace slice

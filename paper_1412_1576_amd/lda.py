@@ -49,7 +49,8 @@ class lda_options(C.Structure):
         ("time_sweep_passes", C.c_int32),
         ("record_bucket_tokens", C.c_int32),
         ("doc_refresh", C.c_int32),
-        ("reserved", C.c_int32 * 6),
+        ("stream_block_tokens", C.c_int32),
+        ("reserved", C.c_int32 * 5),
     ]
 
 
@@ -122,7 +123,8 @@ class Lda:
     def __init__(self, doc_offsets, word_ids, V, K, alpha, beta, seed=0, stream=None,
                  dense_rows=0, dense_alias_min_count=0, proposal_mode=0, sweep_chunk_tokens=0,
                  sweep_block_threads=0, rebuild_tile_tokens=0, time_sweep_passes=0,
-                 record_bucket_tokens=0, doc_refresh=0, dev_alloc=None, dev_free=None):
+                 record_bucket_tokens=0, doc_refresh=0, stream_block_tokens=0, dev_alloc=None,
+                 dev_free=None):
         """dev_alloc(bytes) -> device address (0: failure) and dev_free(address): the
         caller's device allocator for every buffer of the context (both or neither)."""
         L = load_library()
@@ -140,6 +142,7 @@ class Lda:
         opt.time_sweep_passes = time_sweep_passes
         opt.record_bucket_tokens = record_bucket_tokens
         opt.doc_refresh = doc_refresh
+        opt.stream_block_tokens = stream_block_tokens
         # the ctypes thunks must outlive the context: the library calls them until lda_destroy
         self._alloc_cb = self._free_cb = None
         if dev_alloc is not None:

@@ -37,7 +37,7 @@ def test_exports_every_declared_symbol(lib):
 
 def test_options_struct_layout():
     from paper_1412_1576_amd import lda
-    # stream, the three allocator fields, 9 int32, 6 reserved int32
+    # stream, the three allocator fields, 10 int32, 5 reserved int32
     assert C.sizeof(lda.lda_options) == 4 * 8 + 15 * 4 + 4  # padded to 8-byte alignment
     assert lda.lda_options.dev_alloc.offset == 8
     assert lda.lda_options.dense_rows.offset == 32

@@ -27,7 +27,7 @@ def lda_mod():
 
 
 def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12, seed=123,
-                  min_count=0, dense_rows=0, lazy_rows=False):
+                  min_count=0, dense_rows=0, lazy_rows=False, stream_block_tokens=0):
     """min_count > 0: words with fewer tokens draw from the mixture (bench.py's default form).
     min_count < 0: bench.py's rule for the hybrid store -- dense tables only for words with at
     least K tokens and more tokens than any word without a dense row.  dense_rows: as
@@ -39,7 +39,8 @@ def sampled_check(lda_mod, oracle_mod, cfg, mh_steps, n_tokens=2000, n_words=12,
     if min_count < 0:
         min_count = max(int(freq[max(dense_rows, 0):].max()) + 1, cfg.K)
     g = lda_mod.Lda(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
-                    dense_rows=dense_rows, dense_alias_min_count=min_count)
+                    dense_rows=dense_rows, dense_alias_min_count=min_count,
+                    stream_block_tokens=stream_block_tokens)
     o = oracle_mod.Oracle(doff, words, cfg.V, cfg.K, cfg.alpha, cfg.beta, seed=cfg.lib_seed,
                           dense_alias_min_count=min_count, lazy_alias=True, lazy_rows=lazy_rows)
     # initial state: exhaustive
@@ -207,6 +208,16 @@ def test_c5_full_size_sampled(lda_mod, oracle_mod):
     cfg = corpus.CONFIGS["c5"]
     sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10, min_count=-1,
                   dense_rows=-1, lazy_rows=True)
+
+
+@pytest.mark.timeout(1100)
+def test_c5_full_size_streamed_blocks(lda_mod, oracle_mod):
+    """The K = 10^6 slice as its workload words it: 5 * 10^8 tokens streamed from pinned host
+    memory in five blocks of 10^8 tokens (lda_options.stream_block_tokens).  Same checks as
+    the resident run: initial state, rows, tables, sampled chains and n_k against the oracle."""
+    cfg = corpus.CONFIGS["c5"]
+    sampled_check(lda_mod, oracle_mod, cfg, cfg.mh_steps, n_tokens=1500, n_words=10, min_count=-1,
+                  dense_rows=-1, lazy_rows=True, stream_block_tokens=100_000_000)
 
 
 def property_check(lda_mod, cfg, dense_rows, mh_steps, seed=5):
