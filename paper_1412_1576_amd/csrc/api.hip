@@ -92,7 +92,7 @@ void free_all(lda_ctx* c)
     c->side_fork = c->side_join = nullptr;
     c->side_stream = nullptr;
     dev_free(c, c->d_woff); dev_free(c, c->d_nkw); dev_free(c, c->d_nk);
-    dev_free(c, c->d_alias); dev_free(c, c->d_cap); dev_free(c, c->d_chunk_doc); dev_free(c, c->d_tokdoc); dev_free(c, c->d_chunk_doc2); dev_free(c, c->d_tokdoc2); dev_free(c, c->d_long_doc);
+    dev_free(c, c->d_alias); dev_free(c, c->d_cap); dev_free(c, c->d_chunk_doc); dev_free(c, c->d_chunk_tok); dev_free(c, c->d_tokdoc); dev_free(c, c->d_chunk_doc2); dev_free(c, c->d_chunk_tok2); dev_free(c, c->d_tokdoc2); dev_free(c, c->d_long_doc);
     dev_free(c, c->d_long_slot); dev_free(c, c->d_long_keys); dev_free(c, c->d_long_cnts); dev_free(c, c->d_long_first);
     dev_free(c, c->d_tiles); dev_free(c, c->d_multi_words); dev_free(c, c->d_partial); dev_free(c, c->d_row);
     dev_free(c, c->d_flag);
@@ -478,12 +478,14 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     TRY(dev_alloc(c, &c->d_nkw, VK, "n_kw"));
     // rows of list-only words (kKindListOnly) are never written: all zero from here on
     if (hybrid) TRY_HIP(hipMemsetAsync(c->d_nkw, 0, sizeof(int32_t) * VK, c->stream));
-    TRY(dev_alloc(c, &c->d_nk, (size_t)K, "n_k"));
+    TRY(dev_alloc(c, &c->d_nk, (size_t)K + 3, "n_k"));  // read 16 bytes at a time by the doc pass
     TRY(dev_alloc(c, &c->d_cap, (size_t)V, "alias capacities"));
     TRY(dev_alloc(c, &c->d_chunk_doc, chunk_doc.size(), "document tiles"));
+    TRY(dev_alloc(c, &c->d_chunk_tok, chunk_doc.size(), "document tiles"));
     TRY(dev_alloc(c, &c->d_tokdoc, (size_t)N, "token document indices"));
     if (c->n_chunks2 > 0) {
         TRY(dev_alloc(c, &c->d_chunk_doc2, chunk_doc2.size(), "document tiles"));
+        TRY(dev_alloc(c, &c->d_chunk_tok2, chunk_doc2.size(), "document tiles"));
         TRY(dev_alloc(c, &c->d_tokdoc2, (size_t)N, "token document indices"));
     }
     TRY(dev_alloc(c, &c->d_long_doc, (size_t)c->n_long, "long documents"));
@@ -502,9 +504,17 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
                            hipMemcpyHostToDevice, c->stream));
     TRY_HIP(hipMemcpyAsync(c->d_chunk_doc, chunk_doc.data(), sizeof(int32_t) * chunk_doc.size(),
                            hipMemcpyHostToDevice, c->stream));
-    if (c->n_chunks2 > 0)
+    std::vector<int32_t> chunk_tok(chunk_doc.size()), chunk_tok2(chunk_doc2.size());
+    for (size_t i = 0; i < chunk_doc.size(); ++i) chunk_tok[i] = c->h_doff[chunk_doc[i]];
+    for (size_t i = 0; i < chunk_doc2.size(); ++i) chunk_tok2[i] = c->h_doff[chunk_doc2[i]];
+    TRY_HIP(hipMemcpyAsync(c->d_chunk_tok, chunk_tok.data(), sizeof(int32_t) * chunk_tok.size(),
+                           hipMemcpyHostToDevice, c->stream));
+    if (c->n_chunks2 > 0) {
         TRY_HIP(hipMemcpyAsync(c->d_chunk_doc2, chunk_doc2.data(), sizeof(int32_t) * chunk_doc2.size(),
                                hipMemcpyHostToDevice, c->stream));
+        TRY_HIP(hipMemcpyAsync(c->d_chunk_tok2, chunk_tok2.data(), sizeof(int32_t) * chunk_tok2.size(),
+                               hipMemcpyHostToDevice, c->stream));
+    }
     if (c->n_long > 0)
         TRY_HIP(hipMemcpyAsync(c->d_long_doc, c->h_long_doc.data(), sizeof(int32_t) * c->n_long,
                                hipMemcpyHostToDevice, c->stream));

@@ -119,6 +119,7 @@ struct lda_ctx {
     uint32_t* d_cap = nullptr;  // [V] bin capacity of the word's table
     // sweep tiling: chunk c covers documents [chunk_doc[c], chunk_doc[c+1])
     int32_t* d_chunk_doc = nullptr;
+    int32_t* d_chunk_tok = nullptr;  // [n_chunks+1] first token of chunk c (= doff[chunk_doc[c]])
     uint8_t* d_tokdoc = nullptr;     // [N] index of the token's document inside its tile
     int32_t n_chunks = 0;
     int32_t chunk_tokens = 0, chunk_docs = 0, sweep_block = 0;
@@ -126,6 +127,7 @@ struct lda_ctx {
     // of at most two steps (n_chunks2 == 0: not built).  A document is "long" under both
     // tilings when it exceeds chunk_tokens.
     int32_t* d_chunk_doc2 = nullptr;
+    int32_t* d_chunk_tok2 = nullptr;
     uint8_t* d_tokdoc2 = nullptr;
     int32_t n_chunks2 = 0;
     int32_t chunk_tokens2 = 0, chunk_docs2 = 0, sweep_block2 = 0;

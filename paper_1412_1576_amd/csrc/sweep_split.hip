@@ -103,6 +103,7 @@ struct SplitArgs {
     int32_t* znew;
     const int32_t* doff;
     const int32_t* chunk_doc;
+    const int32_t* chunk_tok;  // doff[chunk_doc[c]]: a tile's tokens without the second lookup
     const uint8_t* tokdoc;
     const int32_t* wpos;
     const int32_t* xmap;  // word-major position -> record position (NULL: identity)
@@ -616,8 +617,8 @@ __device__ __forceinline__ void tile_issue_positions(const SplitArgs& A, int32_t
     if (!t.valid) return;
     t.d0 = A.chunk_doc[c];
     t.d1 = A.chunk_doc[c + 1];
-    t.tok0 = A.doff[t.d0];
-    t.ntok = A.doff[t.d1] - t.tok0;
+    t.tok0 = A.chunk_tok[c];
+    t.ntok = A.chunk_tok[c + 1] - t.tok0;
     // nothing / a long document (the long-document kernel's)
     t.valid = !(t.ntok == 0 || (t.d1 - t.d0 == 1 && t.ntok > A.max_doc_tokens));
     if (!t.valid) return;
@@ -739,8 +740,12 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && NW + ND <= 2) ? (MAXB <= 256 ? 7 :
     extern __shared__ int32_t smem[];
     const int32_t* __restrict__ nk = A.nk;
     if constexpr (NKL) {
+        // 16 bytes per load: a quarter of the load and store instructions of a dword copy (n_k is
+        // allocated, and the LDS copy sized, up to the next multiple of 4 topics)
         int32_t* nk_lds = smem + A.tile_lds_ints;
-        for (int32_t k = threadIdx.x; k < A.K; k += blockDim.x) nk_lds[k] = A.nk[k];
+        const int4* __restrict__ src = reinterpret_cast<const int4*>(A.nk);
+        int4* dst = reinterpret_cast<int4*>(nk_lds);
+        for (int32_t k = threadIdx.x; k < (A.K + 3) / 4; k += blockDim.x) dst[k] = src[k];
         nk = nk_lds;  // the staging's first barrier below makes it visible
     }
     const int32_t c = xcd_contiguous(A.n_chunks);
@@ -836,7 +841,7 @@ template <int NW, int ND, int T>
 int launch_doc_tiles(lda_ctx* c, const SplitArgs& A, size_t lds)
 {
     if (c->K <= kNkLdsTopics) {  // with the workgroup's own copy of n_k
-        lds += sizeof(int32_t) * (size_t)c->K;
+        lds += sizeof(int32_t) * (size_t)((c->K + 3) / 4 * 4);
         if (A.doc_block <= 256) return launch_doc_tiles_as<NW, ND, T, 256, true>(c, A, lds);
         if (A.doc_block <= 768) return launch_doc_tiles_as<NW, ND, T, 768, true>(c, A, lds);
         return launch_doc_tiles_as<NW, ND, T, 1024, true>(c, A, lds);
@@ -1024,18 +1029,23 @@ int launch_sweep_split(lda_ctx* c, int32_t mh_steps)
                       (nd == 0 || (c->td_valid && c->td_sweep == c->sweep_index && c->td_nw == nw &&
                                    c->td_nd == nd));
     SplitArgs A{};
-    A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff; A.chunk_doc = c->d_chunk_doc;
+    A.z = c->d_z; A.znew = c->d_znew; A.doff = c->d_doff; A.chunk_doc = c->d_chunk_doc; A.chunk_tok = c->d_chunk_tok;
     A.tokdoc = c->d_tokdoc; A.wpos = c->d_wpos; A.xmap = c->d_xmap; A.gid = c->d_gid; A.woff = c->d_woff;
     A.nkw = c->d_nkw; A.nk = c->d_nk; A.alias = c->d_alias; A.cap = c->d_cap;
     A.zt = c->d_zt; A.zt_pack16 = c->zt_pack16 ? 1 : 0; A.rec = c->d_rec; A.row_items = c->d_row_items; A.pieces = c->d_gather_pieces;
     A.n_chunks = c->n_chunks; A.n_row_items = c->n_row_items; A.n_pieces = c->n_gather_pieces;
     A.K = c->K; A.cap_tokens = c->chunk_tokens; A.max_doc_tokens = c->chunk_tokens;
     A.doc_block = c->sweep_block;
-    A.tile_lds_ints = (int32_t)(doc_tile_lds_bytes(c->chunk_tokens, c->chunk_docs) / sizeof(int32_t));
+    // (rounded up to 16 bytes: the copy of n_k behind the tile is moved as int4)
+    auto tile_ints = [](int32_t tokens, int32_t docs) {
+        return (int32_t)((doc_tile_lds_bytes(tokens, docs) / sizeof(int32_t) + 3) / 4 * 4);
+    };
+    A.tile_lds_ints = tile_ints(c->chunk_tokens, c->chunk_docs);
     if (nw + nd <= 2 && c->n_chunks2 > 0) {  // short chains: the tiling with larger tiles
-        A.chunk_doc = c->d_chunk_doc2; A.tokdoc = c->d_tokdoc2; A.n_chunks = c->n_chunks2;
+        A.chunk_doc = c->d_chunk_doc2; A.chunk_tok = c->d_chunk_tok2; A.tokdoc = c->d_tokdoc2;
+        A.n_chunks = c->n_chunks2;
         A.cap_tokens = c->chunk_tokens2; A.doc_block = c->sweep_block2;
-        A.tile_lds_ints = (int32_t)(doc_tile_lds_bytes(c->chunk_tokens2, c->chunk_docs2) / sizeof(int32_t));
+        A.tile_lds_ints = tile_ints(c->chunk_tokens2, c->chunk_docs2);
     } else if (c->n_chunks2 > 0) {
         // longer chains (default tiles): one token per thread keeps the chain's registers low
         // enough for two 1024-thread workgroups per CU (4 steps: 28.9 instead of 33.4 ms)
