@@ -48,12 +48,15 @@ def doc_pass_bytes_per_token(mh_steps: int) -> float:
     return 36.0 + 12.0 * nw + 16.0 * nd
 
 
-# HBM-side bytes per launch of the doc pass kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs of this command (profiles/all_kernels_c3_mh2.txt: counter KiB x calibration factor x 1024,
-# fetched + written); keyed by (workload, mh_steps, dense_alias_min_count).  None where not
-# measured.
+# HBM-side bytes per launch of the doc pass kernel and of the word pass's gather kernel, from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command (profiles/all_kernels_<workload>_mh2.txt:
+# counter KiB x calibration factor x 1024, fetched + written); keyed by (workload, mh_steps,
+# dense_alias_min_count as passed to the library).  None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2, 10000): (17_724_965.2 * 2.000 + 12_911_892.6 * 1.000) * 1024.0,
+    ("c3", 2, 10000): {"doc_pass_tiles_kernel": 49.79e9},
+    ("c2", 2, 1000): {"doc_pass_tiles_kernel": 6.73e9},
+    ("c4", 2, None): {"doc_pass_tiles_kernel": 89.22e9, "word_pass_gather_kernel": 127.13e9},
+    ("c5", 2, None): {"doc_pass_tiles_kernel": 104.62e9, "word_pass_gather_kernel": 199.59e9},
 }
 
 
@@ -274,14 +277,18 @@ def main():
 
     ms_per_step = total_ms / args.steps
     abytes = algorithmic_bytes_per_token(args.mh_steps)
+    dom_ms = sweep_ms
     if len(pass_ms) == args.steps:
         word_ms = sum(p[0] for p in pass_ms) / args.steps
         doc_ms = sum(p[1] for p in pass_ms) / args.steps
-        dominant, dbytes = "doc_pass_tiles_kernel", doc_pass_bytes_per_token(args.mh_steps)
+        dominant, dbytes, dom_ms = "doc_pass_tiles_kernel", doc_pass_bytes_per_token(args.mh_steps), doc_ms
+        if args.workload in ("c4", "c5") and word_ms > doc_ms:
+            # every token of these stores goes through the one gather kernel of the word pass
+            dominant, dbytes, dom_ms = "word_pass_gather_kernel", abytes - dbytes, word_ms
     else:
         word_ms, doc_ms = None, sweep_ms
         dominant, dbytes = "sweep_tiles_kernel", abytes
-    achieved = dbytes * N / (doc_ms * 1e-3) / 1e9
+    achieved = dbytes * N / (dom_ms * 1e-3) / 1e9
     out = {
         "metric": "sampled tokens/sec (alias build + %d-step MH sweep + count rebuild)" % args.mh_steps,
         "value": N / (ms_per_step * 1e-3),
@@ -312,9 +319,10 @@ def main():
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
             "algorithmic_bytes_per_token": dbytes,
-            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name if not args.docs else None,
-                                                   args.mh_steps,
-                                                   hybrid.get("dense_alias_min_count", 0))),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(
+                (cfg.name if not (args.docs or args.stream_block_tokens) else None, args.mh_steps,
+                 None if args.workload in ("c4", "c5") else hybrid.get("dense_alias_min_count", 0)),
+                {}).get(dominant),
         },
     }
     g.close()
