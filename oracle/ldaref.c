@@ -637,7 +637,7 @@ int ldaref_sweep(ldaref_ctx* c, int32_t mh_steps)
 }
 
 /* Sweep with the doc side refreshed after every token (Sec. 4.2, footnote 4: the doc-proposal
- * "changes after every token to reflect the current state" of the document's assignments)
+ * is not frozen during a document but follows the document's assignments token by token)
  * while the word side -- n_kw, n_k and the word-proposal tables -- stays at the snapshot
  * (Sec. 6, the immutable model slice).  The tokens of a document are visited in order; token
  * i sees the topics that tokens < i of the same document were just given, in n_kd and in the

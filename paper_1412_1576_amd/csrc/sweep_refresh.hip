@@ -1,6 +1,5 @@
 // Sweep with the doc side refreshed after every token (LightLDA Sec. 4.2, footnote 4: the
-// doc-proposal changes after every token to reflect the current state of the document's
-// assignments) and the word side -- n_kw, n_k, the word-proposal tables -- kept at the snapshot
+// doc-proposal is not frozen during a document but follows its assignments token by token) and the word side -- n_kw, n_k, the word-proposal tables -- kept at the snapshot
 // (Sec. 6, the immutable model slice).  Selected by lda_options.doc_refresh.
 //
 // The tokens of a document are visited in order, so a document is a sequential chain; the
