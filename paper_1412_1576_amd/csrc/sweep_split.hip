@@ -67,6 +67,18 @@ struct Chain {
     __host__ __device__ static constexpr int rec_doc(int i) { return 1 + 2 * NW + i; }
 };
 
+// A word step's record carries, above the proposed topic (topics take kTopicBits bits), the top
+// bits of the random word x2 that decides the step's accept test.  The word pass has that
+// Philox output anyway (the draw uses the same call); the doc pass can then decide almost
+// every test from the two ends of the interval the bits leave open and needs the generator
+// only when the ends disagree.
+constexpr int kHintShift = kTopicBits;
+constexpr uint32_t kHintSpan = (1u << kHintShift) - 1u;  // x2 is in [hint << shift, (hint << shift) | span]
+__device__ __forceinline__ int32_t topic_with_hint(int32_t t, uint32_t x2)
+{
+    return (int32_t)((uint32_t)t | (x2 & ~kHintSpan));
+}
+
 template <int R>
 __device__ __forceinline__ void load_ints(const int32_t* __restrict__ p, int32_t (&v)[R])
 {
@@ -148,12 +160,6 @@ struct SplitArgs {
 // when every topic fits 16 bits, two fields per int; rounded up to a power of two
 constexpr int zt_record_shift(int nd, bool pack16) { return pow2_shift(pack16 ? (2 + nd) / 2 : 1 + nd); }
 
-// record position of the token at word-major position p
-__device__ __forceinline__ size_t record_at(const SplitArgs& A, int32_t p)
-{
-    return A.xmap ? (size_t)A.xmap[p] : (size_t)p;
-}
-
 // v[0] = z, v[1 + i] = the topic doc step i proposes, of the token whose records are at p
 template <int ND>
 __device__ __forceinline__ void load_zt(const SplitArgs& A, size_t p, int32_t (&v)[1 + ND])
@@ -192,6 +198,60 @@ __device__ __forceinline__ void store_zt(const SplitArgs& A, size_t p, const int
 #pragma unroll
         for (int k = 0; k <= ND; ++k) w[k] = v[k];
         store_ints<W>(A.zt + p * W, w);
+    }
+}
+
+// The word pass's inputs of U tokens of a thread, fetched stage by stage: record position
+// (a load of its own when the records are bucketed) and CSR position, then the packed
+// (z, doc proposals) record.  Whether there is an xmap and how the record is packed is the
+// same for the whole launch; with_record_layout() dispatches on both once, outside the loops,
+// so that the loops are straight-line code in which the U loads of a stage are issued back
+// to back.  (With the two tests inside, every token's loads were issued and awaited one after
+// the other: eight dependent round trips per round of four tokens instead of two.)
+template <int ND, int U, bool XM, bool P16>
+struct TokenFetch {
+    static constexpr int W = 1 << zt_record_shift(ND, P16);
+    size_t q[U];
+    uint32_t g[U];
+    int32_t w[U][W];
+    template <bool GID>
+    __device__ __forceinline__ void positions(const SplitArgs& A, const int32_t (&p)[U])
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if constexpr (XM) q[u] = (size_t)A.xmap[p[u]]; else q[u] = (size_t)p[u];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if constexpr (GID) g[u] = (uint32_t)A.gid[p[u]]; else g[u] = 0u;
+        }
+    }
+    __device__ __forceinline__ void records(const SplitArgs& A)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) load_ints<W>(A.zt + q[u] * W, w[u]);
+    }
+    // v[0] = z, v[1 + i] = the topic doc step i proposes
+    __device__ __forceinline__ void decode(int u, int32_t (&v)[1 + ND]) const
+    {
+#pragma unroll
+        for (int k = 0; k <= ND; ++k) {
+            if constexpr (P16) v[k] = (int32_t)(((uint32_t)w[u][k >> 1] >> (16 * (k & 1))) & 0xFFFFu);
+            else v[k] = w[u][k];
+        }
+    }
+};
+
+template <bool B>
+struct Flag { static constexpr bool value = B; };
+
+template <class F>
+__device__ __forceinline__ void with_record_layout(const SplitArgs& A, F&& f)
+{
+    if (A.xmap) {
+        if (A.zt_pack16) f(Flag<true>{}, Flag<true>{}); else f(Flag<true>{}, Flag<false>{});
+    } else {
+        if (A.zt_pack16) f(Flag<false>{}, Flag<true>{}); else f(Flag<false>{}, Flag<false>{});
     }
 }
 
@@ -256,56 +316,69 @@ __global__ __launch_bounds__(1024) void word_pass_rows_kernel(SplitArgs A)
     const int32_t K = A.K;
     const size_t wk = (size_t)it.x * (size_t)K;
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < K; k += nt) {
-        row[k] = A.nkw[wk + k];
-        if constexpr (NW > 0) {
-            const uint4 e = A.alias[wk + k];
-            tab[k] = make_uint2(e.x, e.y);
+    {
+        // staging: S entries of a thread in flight together
+        constexpr int S = 4;
+        for (int32_t k0 = tid; k0 < K; k0 += S * nt) {
+            int32_t rv[S];
+            uint2 ev[S];
+#pragma unroll
+            for (int q = 0; q < S; ++q) {
+                const int32_t k = k0 + q * nt < K ? k0 + q * nt : K - 1;
+                rv[q] = A.nkw[wk + k];
+                if constexpr (NW > 0) ev[q] = *reinterpret_cast<const uint2*>(&A.alias[wk + k]);
+            }
+#pragma unroll
+            for (int q = 0; q < S; ++q) {
+                const int32_t k = k0 + q * nt < K ? k0 + q * nt : K - 1;  // past the end: the last entry again
+                row[k] = rv[q];
+                if constexpr (NW > 0) tab[k] = ev[q];
+            }
         }
     }
     __syncthreads();
     const uint32_t capw = A.cap[it.x];
-    // U tokens per thread and round: their loads are issued together (the loop is bound by
-    // the latency of one load round trip per round at 4 waves per SIMD)
-    constexpr int U = 4;
-    for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
-        int32_t p[U], zt[U][1 + ND];
-        size_t q[U];
-        uint32_t g[U];
-        bool live[U];
+    with_record_layout(A, [&](auto xm, auto p16) {
+        // U tokens per thread and round, their loads issued together stage by stage
+        constexpr int U = 4;
+        for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
+            int32_t p[U];
+            bool live[U];
+            TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int32_t i = i0 + u * nt + tid;
-            live[u] = i < it.z;
-            if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
-            p[u] = it.y + i;
-            q[u] = record_at(A, p[u]);
-            load_zt<ND>(A, q[u], zt[u]);
-            g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            int32_t out[C::R];
-#pragma unroll
-            for (int k = 0; k < C::R; ++k) out[k] = 0;
-            out[0] = row[zt[u][0]];
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
-                uint32_t x[4];
-                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-                const uint32_t rr = mulhi32(x[1], capw);
-                const uint2 e = tab[bin];
-                const int32_t t = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
-                out[C::rec_topic(k)] = t;
-                out[C::rec_topic(k) + 1] = row[t];
+            for (int u = 0; u < U; ++u) {
+                int32_t i = i0 + u * nt + tid;
+                live[u] = i < it.z;
+                if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
+                p[u] = it.y + i;
             }
+            f.template positions<(NW > 0)>(A, p);
+            f.records(A);
 #pragma unroll
-            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[u][1 + k]];
-            if (live[u]) store_ints<C::R>(A.rec + (q[u] << C::rec_shift), out);
+            for (int u = 0; u < U; ++u) {
+                int32_t zt[1 + ND], out[C::R];
+                f.decode(u, zt);
+#pragma unroll
+                for (int k = 0; k < C::R; ++k) out[k] = 0;
+                out[0] = row[zt[0]];
+#pragma unroll
+                for (int k = 0; k < NW; ++k) {
+                    // Fig. 2: uniform bin, uniform height, keep the bin or take its alias
+                    uint32_t x[4];
+                    philox4x32_10(f.g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                    const uint32_t bin = mulhi32(x[0], (uint32_t)K);
+                    const uint32_t rr = mulhi32(x[1], capw);
+                    const uint2 e = tab[bin];
+                    const int32_t t = (rr < e.x) ? (int32_t)bin : (int32_t)e.y;
+                    out[C::rec_topic(k)] = topic_with_hint(t, x[2]);
+                    out[C::rec_topic(k) + 1] = row[t];
+                }
+#pragma unroll
+                for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
+                if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out);
+            }
         }
-    }
+    });
 }
 
 // The word of word-major position p inside a piece: the last w with off[w] <= p, where
@@ -338,45 +411,79 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
     for (int32_t i = tid; i <= nwords; i += nt) soff[i] = A.woff[pc.x + i];
     __syncthreads();
     if constexpr (STORE == 0) {
-        for (int32_t i = tid; i < pc.w; i += nt) {
-            const int32_t p = pc.z + i;
-            const int32_t w = pc.x + piece_word(soff, nwords, p);
-            int32_t zt[1 + ND], out[C::R];
-            const size_t q = record_at(A, p);
-            load_zt<ND>(A, q, zt);
+        with_record_layout(A, [&](auto xm, auto p16) {
+            constexpr int U = 4;
+            for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
+                int32_t p[U], zt[U][1 + ND], out[U][C::R];
+                size_t wk[U];
+                uint32_t capw[U];
+                bool live[U];
+                TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
 #pragma unroll
-            for (int k = 0; k < C::R; ++k) out[k] = 0;
-            const size_t wk = (size_t)w * (size_t)K;
-            out[0] = A.nkw[wk + (size_t)zt[0]];
-            if constexpr (NW > 0) {
-                const uint32_t g = (uint32_t)A.gid[p];
-                const uint32_t capw = A.cap[w];
+                for (int u = 0; u < U; ++u) {
+                    int32_t i = i0 + u * nt + tid;
+                    live[u] = i < pc.w;
+                    if (!live[u]) i = pc.w - 1;  // redo the piece's last token, drop the result
+                    p[u] = pc.z + i;
+                }
+                f.template positions<(NW > 0)>(A, p);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int32_t w = pc.x + piece_word(soff, nwords, p[u]);
+                    wk[u] = (size_t)w * (size_t)K;
+                    capw[u] = (NW > 0) ? A.cap[w] : 0u;
+                }
+                f.records(A);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    f.decode(u, zt[u]);
+#pragma unroll
+                    for (int k = 0; k < C::R; ++k) out[u][k] = 0;
+                }
+                // every gather of the round before the first use
+                uint4 e[NW > 0 ? NW : 1][U];
+                uint32_t bin[NW > 0 ? NW : 1][U], rr[NW > 0 ? NW : 1][U], hint[NW > 0 ? NW : 1][U];
 #pragma unroll
                 for (int k = 0; k < NW; ++k) {
-                    uint32_t x[4];
-                    philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                    const uint32_t bin = mulhi32(x[0], (uint32_t)K);
-                    const uint32_t rr = mulhi32(x[1], capw);
-                    const uint4 e = A.alias[wk + bin];  // brings n_kw of both outcomes along
-                    const bool keep = rr < e.x;
-                    out[C::rec_topic(k)] = keep ? (int32_t)bin : (int32_t)e.y;
-                    out[C::rec_topic(k) + 1] = keep ? (int32_t)e.z : (int32_t)e.w;
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        uint32_t x[4];
+                        philox4x32_10(f.g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                        bin[k][u] = mulhi32(x[0], (uint32_t)K);
+                        rr[k][u] = mulhi32(x[1], capw[u]);
+                        hint[k][u] = x[2];
+                        e[k][u] = A.alias[wk[u] + bin[k][u]];  // brings n_kw of both outcomes along
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    out[u][0] = A.nkw[wk[u] + (size_t)zt[u][0]];
+#pragma unroll
+                    for (int k = 0; k < ND; ++k) out[u][C::rec_doc(k)] = A.nkw[wk[u] + (size_t)zt[u][1 + k]];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+#pragma unroll
+                    for (int k = 0; k < NW; ++k) {
+                        const bool keep = rr[k][u] < e[k][u].x;
+                        out[u][C::rec_topic(k)] =
+                            topic_with_hint(keep ? (int32_t)bin[k][u] : (int32_t)e[k][u].y, hint[k][u]);
+                        out[u][C::rec_topic(k) + 1] = keep ? (int32_t)e[k][u].z : (int32_t)e[k][u].w;
+                    }
+                    if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out[u]);
                 }
             }
-#pragma unroll
-            for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = A.nkw[wk + (size_t)zt[1 + k]];
-            store_ints<C::R>(A.rec + (q << C::rec_shift), out);
-        }
+        });
     } else {
-        constexpr int U = 2;
         BetaTable bt{};
         if constexpr (NW > 0) bt = load_beta_table(A);
+        with_record_layout(A, [&](auto xm, auto p16) {
+        constexpr int U = 2;
         for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
             int32_t p[U], zt[U][1 + ND], out[U][C::R];
-            size_t q[U];
             bool live[U];
             WordSide wv[U];
-            uint32_t g[U];
+            TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // lanes past the end of the piece redo its last token and drop the result
@@ -384,10 +491,16 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
                 live[u] = i < pc.w;
                 if (!live[u]) i = pc.w - 1;
                 p[u] = pc.z + i;
-                q[u] = record_at(A, p[u]);
-                load_zt<ND>(A, q[u], zt[u]);
-                g[u] = (NW > 0) ? (uint32_t)A.gid[p[u]] : 0u;
-                wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
+            }
+            f.template positions<(NW > 0)>(A, p);
+#pragma unroll
+            for (int u = 0; u < U; ++u) wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
+            f.records(A);
+            const uint32_t (&g)[U] = f.g;
+            const size_t (&q)[U] = f.q;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                f.decode(u, zt[u]);
 #pragma unroll
                 for (int k = 0; k < C::R; ++k) out[u][k] = 0;
             }
@@ -402,12 +515,14 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
                 uint4 e[U];
                 int32_t t[U], nwt[U];
                 bool known[U];
+                uint32_t hint[U];
                 NkwProbe pb[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     uint32_t x[4];
                     philox4x32_10(g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
                     e[u] = *word_draw_address(wv[u], bt, (uint32_t)K, x[0], x[1], x[3], d[u]);
+                    hint[u] = x[2];
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -417,7 +532,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if (!known[u]) nwt[u] = nkw_probe_finish<STORE>(wv[u], t[u], pb[u]);
-                    out[u][C::rec_topic(k)] = t[u];
+                    out[u][C::rec_topic(k)] = topic_with_hint(t[u], hint[u]);
                     out[u][C::rec_topic(k) + 1] = nwt[u];
                 }
             }
@@ -430,6 +545,7 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
                 if (live[u]) store_ints<C::R>(A.rec + (q[u] << C::rec_shift), out[u]);
             }
         }
+        });
     }
 }
 
@@ -459,32 +575,56 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
     const WordSide wv = load_word<1>(A, w);
     BetaTable bt{};
     if constexpr (NW > 0) bt = load_beta_table(A);
-    for (int32_t i = tid; i < it.z; i += nt) {
-        const int32_t p = it.y + i;
-        int32_t zt[1 + ND], out[C::R];
-        const size_t q = record_at(A, p);
-        load_zt<ND>(A, q, zt);
+    with_record_layout(A, [&](auto xm, auto p16) {
+        constexpr int U = 2;
+        for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
+            int32_t p[U], zt[U][1 + ND], out[U][C::R];
+            bool live[U];
+            TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
 #pragma unroll
-        for (int k = 0; k < C::R; ++k) out[k] = 0;
-        out[0] = row[zt[0]];
-        if constexpr (NW > 0) {
-            const uint32_t g = (uint32_t)A.gid[p];
+            for (int u = 0; u < U; ++u) {
+                int32_t i = i0 + u * nt + tid;
+                live[u] = i < it.z;
+                if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
+                p[u] = it.y + i;
+            }
+            f.template positions<(NW > 0)>(A, p);
+            f.records(A);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                f.decode(u, zt[u]);
+#pragma unroll
+                for (int k = 0; k < C::R; ++k) out[u][k] = 0;
+                out[u][0] = row[zt[u][0]];
+            }
 #pragma unroll
             for (int k = 0; k < NW; ++k) {
-                uint32_t x[4];
-                philox4x32_10(g, 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                WordDraw d;
-                const uint4 e = *word_draw_address(wv, bt, (uint32_t)K, x[0], x[1], x[3], d);
-                int32_t t, nwt;
-                if (!word_draw_decode(d, e, t, nwt)) nwt = row[t];
-                out[C::rec_topic(k)] = t;
-                out[C::rec_topic(k) + 1] = nwt;
+                WordDraw d[U];
+                uint4 e[U];
+                uint32_t hint[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    uint32_t x[4];
+                    philox4x32_10(f.g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                    e[u] = *word_draw_address(wv, bt, (uint32_t)K, x[0], x[1], x[3], d[u]);
+                    hint[u] = x[2];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    int32_t t, nwt;
+                    if (!word_draw_decode(d[u], e[u], t, nwt)) nwt = row[t];
+                    out[u][C::rec_topic(k)] = topic_with_hint(t, hint[u]);
+                    out[u][C::rec_topic(k) + 1] = nwt;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int k = 0; k < ND; ++k) out[u][C::rec_doc(k)] = row[zt[u][1 + k]];
+                if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out[u]);
             }
         }
-#pragma unroll
-        for (int k = 0; k < ND; ++k) out[C::rec_doc(k)] = row[zt[1 + k]];
-        store_ints<C::R>(A.rec + (q << C::rec_shift), out);
-    }
+    });
 }
 
 // ---- doc pass ------------------------------------------------------------------------
@@ -544,14 +684,16 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
         const int i = C::index(j);
 #pragma unroll
         for (int u = 0; u < T; ++u) {
-            uint32_t x[4];
-            philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
-            x2[j][u] = x[2];
             if (word_step) {
-                t[j][u] = r[u][C::rec_topic(i)];
+                // the record's topic int: the topic, and above it the top bits of x2
+                x2[j][u] = (uint32_t)r[u][C::rec_topic(i)] & ~kHintSpan;
+                t[j][u] = (int32_t)((uint32_t)r[u][C::rec_topic(i)] & kHintSpan);
                 nwt[j][u] = r[u][C::rec_topic(i) + 1];
                 ndt[j][u] = doc[u].count(t[j][u]);
             } else {
+                uint32_t x[4];
+                philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                x2[j][u] = x[2];
                 const double u0 = unit_open(x[0]);
                 const double Ld = (double)doc[u].L;
                 if (u0 * (Ld + A.alphabar) < Ld) {
@@ -589,8 +731,23 @@ __device__ __forceinline__ void doc_pass_chains(const SplitArgs& A, const DocVie
                 num = num * ((double)nds[u] + A.alpha);
                 den = den * ((double)nd_t + A.alpha);
             }
-            const double uu = unit_open(x2[j][u]);
-            const bool accept = (tt != s[u]) && (uu * den < num);
+            bool accept;
+            if (word_step) {
+                // x2 is known up to its low bits.  The test is monotone in x2 (a rounded product
+                // of a positive number is monotone), so if both ends of the interval agree the
+                // test is decided; if they differ in any lane, the wave draws the number itself.
+                const bool at_low = unit_open(x2[j][u]) * den < num;
+                const bool at_high = unit_open(x2[j][u] | kHintSpan) * den < num;
+                accept = at_high;
+                if (__any((at_low != at_high) && (tt != s[u]))) {
+                    uint32_t x[4];
+                    philox4x32_10(g[u], 0u, A.sweep, (uint32_t)j, A.seed_lo, A.seed_hi, x);
+                    accept = unit_open(x[2]) * den < num;
+                }
+            } else {
+                accept = unit_open(x2[j][u]) * den < num;
+            }
+            accept = accept && (tt != s[u]);
             s[u] = accept ? tt : s[u];
             nds[u] = accept ? nd_t : nds[u];
             nws[u] = accept ? nw_t : nws[u];
@@ -606,6 +763,7 @@ struct TileTokens {
     bool valid;                  // uniform: a tile this kernel handles
     uint32_t g[T];
     int32_t wp[T], idx[T], z0[T], dl[T], r[T][R];
+    int32_t doc_end;             // doff of the thread's own document of the tile (clamped to the last)
     bool live[T];
 };
 
@@ -632,20 +790,24 @@ __device__ __forceinline__ void tile_issue_positions(const SplitArgs& A, int32_t
         t.g[u] = (uint32_t)(t.tok0 + i);
         t.wp[u] = __builtin_nontemporal_load(&A.wpos[t.g[u]]);
     }
+    // Loads return in the order they were issued: what the staging of the documents needs is
+    // requested before the record gather, so that the staging does not wait for the gather.
+#pragma unroll
+    for (int u = 0; u < T; ++u) {
+        t.z0[u] = __builtin_nontemporal_load(&A.z[t.g[u]]);
+        t.dl[u] = (int32_t)__builtin_nontemporal_load(&A.tokdoc[t.g[u]]);
+    }
+    const int32_t nd = t.d1 - t.d0;
+    t.doc_end = A.doff[t.d0 + ((int32_t)threadIdx.x < nd ? (int32_t)threadIdx.x : nd)];
 }
 
-// second half: the word-pass records (one random line per token), snapshot topics, documents
+// second half: the word-pass records (one random line per token)
 template <int T, int R, int RS>
 __device__ __forceinline__ void tile_issue_records(const SplitArgs& A, TileTokens<T, R>& t)
 {
     if (!t.valid) return;
 #pragma unroll
     for (int u = 0; u < T; ++u) load_ints<R>(A.rec + ((size_t)t.wp[u] << RS), t.r[u]);
-#pragma unroll
-    for (int u = 0; u < T; ++u) {
-        t.z0[u] = __builtin_nontemporal_load(&A.z[t.g[u]]);
-        t.dl[u] = (int32_t)__builtin_nontemporal_load(&A.tokdoc[t.g[u]]);
-    }
 }
 
 // Stage the tile as load_doc_tile does (doc_tile.hpp: same LDS layout, same tables) but keep
@@ -667,7 +829,9 @@ __device__ __forceinline__ void tile_process(const SplitArgs& A, int32_t* smem,
     tile.ntok = t.ntok;
     int32_t nd0[T], s[T];
     uint32_t slot[T];
-    for (int32_t i = threadIdx.x; i <= tile.nd; i += blockDim.x) tile.sdoff[i] = A.doff[t.d0 + i] - t.tok0;
+    // document offsets inside the tile: a thread's first one was requested with its tokens
+    if ((int32_t)threadIdx.x <= tile.nd) tile.sdoff[threadIdx.x] = t.doc_end - t.tok0;
+    for (int32_t i = threadIdx.x + blockDim.x; i <= tile.nd; i += blockDim.x) tile.sdoff[i] = A.doff[t.d0 + i] - t.tok0;
 #pragma unroll
     for (int u = 0; u < T; ++u) {
         if (t.live[u]) {
@@ -739,23 +903,41 @@ __global__ __launch_bounds__(MAXB, (T <= 2 && NW + ND <= 2) ? (MAXB <= 256 ? 7 :
     using C = Chain<NW, ND>;
     extern __shared__ int32_t smem[];
     const int32_t* __restrict__ nk = A.nk;
+    const int32_t c = xcd_contiguous(A.n_chunks);
+    if (c >= A.n_chunks) return;
+    // Order of the requests: the token streams the staging needs, the first part of n_k, then
+    // the word-pass records (one random line per token, addressed by the first stream).  Loads
+    // complete in order, so the n_k copy and the staging of the documents go ahead while the
+    // gather is still on its way; the chains are the first to need it.
+    TileTokens<T, C::R> t;
+    tile_issue_positions<T, C::R>(A, c, t);
+    if (!t.valid) return;  // uniform over the workgroup
     if constexpr (NKL) {
-        // 16 bytes per load: a quarter of the load and store instructions of a dword copy (n_k is
-        // allocated, and the LDS copy sized, up to the next multiple of 4 topics)
+        // 16 bytes per load (n_k is allocated, and the LDS copy sized, up to the next multiple of
+        // 4 topics); the first kNkAhead loads of a thread are in flight together.  Threads past
+        // the end repeat the last element: same value to the same place, no branch.
+        constexpr int kNkAhead = 4;
+        const int32_t nq = (A.K + 3) / 4;
         int32_t* nk_lds = smem + A.tile_lds_ints;
         const int4* __restrict__ src = reinterpret_cast<const int4*>(A.nk);
         int4* dst = reinterpret_cast<int4*>(nk_lds);
-        for (int32_t k = threadIdx.x; k < (A.K + 3) / 4; k += blockDim.x) dst[k] = src[k];
-        nk = nk_lds;  // the staging's first barrier below makes it visible
+        int4 ahead[kNkAhead];
+        int32_t at[kNkAhead];
+#pragma unroll
+        for (int b = 0; b < kNkAhead; ++b) {
+            const int32_t k = (int32_t)threadIdx.x + b * (int32_t)blockDim.x;
+            at[b] = k < nq ? k : nq - 1;
+            ahead[b] = src[at[b]];
+        }
+        tile_issue_records<T, C::R, C::rec_shift>(A, t);
+#pragma unroll
+        for (int b = 0; b < kNkAhead; ++b) dst[at[b]] = ahead[b];
+        for (int32_t k = threadIdx.x + kNkAhead * blockDim.x; k < nq; k += blockDim.x) dst[k] = src[k];
+        nk = nk_lds;  // the staging's first barrier makes it visible
+    } else {
+        tile_issue_records<T, C::R, C::rec_shift>(A, t);
     }
-    const int32_t c = xcd_contiguous(A.n_chunks);
-    if (c >= A.n_chunks) return;
-    // the word-pass records do not depend on the tile: their gather (one random line per
-    // token) is issued first and overlaps the staging of the documents
-    TileTokens<T, C::R> t;
-    tile_issue_positions<T, C::R>(A, c, t);
-    tile_issue_records<T, C::R, C::rec_shift>(A, t);
-    if (t.valid) tile_process<NW, ND, T>(A, smem, nk, t);
+    tile_process<NW, ND, T>(A, smem, nk, t);
 }
 
 template <int NW, int ND>
