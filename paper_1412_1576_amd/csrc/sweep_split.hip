@@ -36,7 +36,11 @@ namespace {
 
 constexpr int32_t kRowItemTokens = 65536;  // tokens a workgroup serves from one staging of the rows
 constexpr int32_t kRowMinTokens = 2048;    // words with fewer tokens are gathered
-constexpr int32_t kPieceTokens = 4096;     // tokens of a gather piece
+// Tokens of a gather piece.  Small on purpose: a piece is one workgroup, some 200 of them are
+// in flight on an XCD, and what they gather from -- the hash rows and tables of their words --
+// has to fit that XCD's 4 MB of L2 to be reused by a word's later tokens.  With 4096-token
+// pieces the words in flight held 30 MB and three of four gathers missed.
+constexpr int32_t kPieceTokens = 512;
 constexpr int32_t kPieceWords = 4096;      // words of a gather piece (their offsets sit in LDS)
 
 constexpr int pow2_shift(int n)
@@ -255,7 +259,7 @@ __device__ __forceinline__ void with_record_layout(const SplitArgs& A, F&& f)
     }
 }
 
-constexpr int32_t kRowItemRun = 8, kMixItemRun = 16, kPieceRun = 64;
+constexpr int32_t kRowItemRun = 8, kMixItemRun = 16, kPieceRun = 256;
 
 // Eq. (9), (12): the topic of a random token of the document, or a uniform topic.
 // zat(j) is the snapshot topic of the document's j-th token.
@@ -478,73 +482,106 @@ __global__ __launch_bounds__(256) void word_pass_gather_kernel(SplitArgs A)
         BetaTable bt{};
         if constexpr (NW > 0) bt = load_beta_table(A);
         with_record_layout(A, [&](auto xm, auto p16) {
-        constexpr int U = 2;
-        for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
-            int32_t p[U], zt[U][1 + ND], out[U][C::R];
-            bool live[U];
-            WordSide wv[U];
-            TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                // lanes past the end of the piece redo its last token and drop the result
-                int32_t i = i0 + u * nt + tid;
-                live[u] = i < pc.w;
-                if (!live[u]) i = pc.w - 1;
-                p[u] = pc.z + i;
-            }
-            f.template positions<(NW > 0)>(A, p);
-#pragma unroll
-            for (int u = 0; u < U; ++u) wv[u] = load_word<STORE>(A, pc.x + piece_word(soff, nwords, p[u]));
-            f.records(A);
-            const uint32_t (&g)[U] = f.g;
-            const size_t (&q)[U] = f.q;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                f.decode(u, zt[u]);
-#pragma unroll
-                for (int k = 0; k < C::R; ++k) out[u][k] = 0;
-            }
-            NkwProbe pr[U][1 + ND];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int k = 0; k <= ND; ++k) pr[u][k] = nkw_probe_begin<STORE>(wv[u], zt[u][k]);
-#pragma unroll
-            for (int k = 0; k < NW; ++k) {
-                WordDraw d[U];
-                uint4 e[U];
-                int32_t t[U], nwt[U];
-                bool known[U];
-                uint32_t hint[U];
-                NkwProbe pb[U];
+            constexpr int U = 2;
+            for (int32_t i0 = 0; i0 < pc.w; i0 += U * nt) {
+                int32_t p[U], w[U], zt[U][1 + ND], out[U][C::R];
+                bool live[U];
+                WordMeta meta[U];
+                WordSide wv[U];
+                TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
+                // stage 1: positions (and CSR positions), the words by bisection of the piece's
+                // offsets in LDS, then every word record and token record
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    uint32_t x[4];
-                    philox4x32_10(g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
-                    e[u] = *word_draw_address(wv[u], bt, (uint32_t)K, x[0], x[1], x[3], d[u]);
-                    hint[u] = x[2];
+                    // lanes past the end of the piece redo its last token and drop the result
+                    int32_t i = i0 + u * nt + tid;
+                    live[u] = i < pc.w;
+                    if (!live[u]) i = pc.w - 1;
+                    p[u] = pc.z + i;
+                }
+                f.template positions<(NW > 0)>(A, p);
+#pragma unroll
+                for (int u = 0; u < U; ++u) w[u] = pc.x + piece_word(soff, nwords, p[u]);
+#pragma unroll
+                for (int u = 0; u < U; ++u) meta[u] = load_word_meta(A, w[u]);
+                f.records(A);
+                uint32_t kinds = 0;
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    wv[u] = word_from_meta<STORE>(A, w[u], meta[u]);
+                    kinds |= wv[u].kind;
+                    f.decode(u, zt[u]);
+#pragma unroll
+                    for (int k = 0; k < C::R; ++k) out[u][k] = 0;
+                }
+                if (__any(kinds & kKindListOnly)) {
+                    // a word whose row is not kept: its lookups search its mixture table
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        out[u][0] = nkw_lookup<STORE>(wv[u], zt[u][0]);
+#pragma unroll
+                        for (int k = 0; k < ND; ++k) out[u][C::rec_doc(k)] = nkw_lookup<STORE>(wv[u], zt[u][1 + k]);
+#pragma unroll
+                        for (int k = 0; k < NW; ++k) {
+                            uint32_t x[4];
+                            philox4x32_10(f.g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                            WordDraw d;
+                            const uint4 e = *word_draw_address(wv[u], bt, (uint32_t)K, x[0], x[1], x[3], d);
+                            int32_t t, nwt;
+                            if (!word_draw_decode(d, e, t, nwt)) nwt = nkw_lookup<STORE>(wv[u], t);
+                            out[u][C::rec_topic(k)] = topic_with_hint(t, x[2]);
+                            out[u][C::rec_topic(k) + 1] = nwt;
+                        }
+                        if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out[u]);
+                    }
+                    continue;
+                }
+                // stage 2: the first probe of every n_kw lookup and the table bin of every draw
+                NkwFetch pr[U][1 + ND];
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int k = 0; k <= ND; ++k) pr[u][k] = nkw_fetch_begin<STORE>(wv[u], zt[u][k]);
+                WordDraw d[NW > 0 ? NW : 1][U];
+                uint4 e[NW > 0 ? NW : 1][U];
+                uint32_t hint[NW > 0 ? NW : 1][U];
+#pragma unroll
+                for (int k = 0; k < NW; ++k) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        uint32_t x[4];
+                        philox4x32_10(f.g[u], 0u, A.sweep, (uint32_t)C::word_step(k), A.seed_lo, A.seed_hi, x);
+                        e[k][u] = *word_draw_address(wv[u], bt, (uint32_t)K, x[0], x[1], x[3], d[k][u]);
+                        hint[k][u] = x[2];
+                    }
+                }
+                // stage 3: the proposals; a draw from the beta term still needs its n_kw
+                int32_t t[NW > 0 ? NW : 1][U], nwt[NW > 0 ? NW : 1][U];
+                bool known[NW > 0 ? NW : 1][U];
+                NkwFetch pb[NW > 0 ? NW : 1][U];
+#pragma unroll
+                for (int k = 0; k < NW; ++k) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u) {
+                        known[k][u] = word_draw_decode(d[k][u], e[k][u], t[k][u], nwt[k][u]);
+                        if (!known[k][u]) pb[k][u] = nkw_fetch_begin<STORE>(wv[u], t[k][u]);
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    known[u] = word_draw_decode(d[u], e[u], t[u], nwt[u]);
-                    if (!known[u]) pb[u] = nkw_probe_begin<STORE>(wv[u], t[u]);
-                }
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (!known[u]) nwt[u] = nkw_probe_finish<STORE>(wv[u], t[u], pb[u]);
-                    out[u][C::rec_topic(k)] = topic_with_hint(t[u], hint[u]);
-                    out[u][C::rec_topic(k) + 1] = nwt[u];
+                    for (int k = 0; k < NW; ++k) {
+                        if (!known[k][u]) nwt[k][u] = nkw_fetch_finish<STORE>(wv[u], t[k][u], pb[k][u]);
+                        out[u][C::rec_topic(k)] = topic_with_hint(t[k][u], hint[k][u]);
+                        out[u][C::rec_topic(k) + 1] = nwt[k][u];
+                    }
+                    out[u][0] = nkw_fetch_finish<STORE>(wv[u], zt[u][0], pr[u][0]);
+#pragma unroll
+                    for (int k = 0; k < ND; ++k)
+                        out[u][C::rec_doc(k)] = nkw_fetch_finish<STORE>(wv[u], zt[u][1 + k], pr[u][1 + k]);
+                    if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out[u]);
                 }
             }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                out[u][0] = nkw_probe_finish<STORE>(wv[u], zt[u][0], pr[u][0]);
-#pragma unroll
-                for (int k = 0; k < ND; ++k)
-                    out[u][C::rec_doc(k)] = nkw_probe_finish<STORE>(wv[u], zt[u][1 + k], pr[u][1 + k]);
-                if (live[u]) store_ints<C::R>(A.rec + (q[u] << C::rec_shift), out[u]);
-            }
-        }
         });
     }
 }

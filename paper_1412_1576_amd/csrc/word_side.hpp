@@ -22,10 +22,22 @@ struct WordSide {
     uint64_t QS;       // integer mass of the sparse term (mixture form)
 };
 
-template <int STORE, class Args>
-__device__ __forceinline__ WordSide load_word(const Args& A, int32_t w)
+// The word's 32-byte record as loaded, and what it says, in two steps: a caller that
+// serves several tokens at once issues all their loads before it looks at any of them.
+struct WordMeta {
+    uint4 a, b;
+};
+
+template <class Args>
+__device__ __forceinline__ WordMeta load_word_meta(const Args& A, int32_t w)
 {
-    const uint4 a = A.metaA[2 * (size_t)w], b = A.metaB[2 * (size_t)w];  // one 32-byte record
+    return WordMeta{A.metaA[2 * (size_t)w], A.metaB[2 * (size_t)w]};
+}
+
+template <int STORE, class Args>
+__device__ __forceinline__ WordSide word_from_meta(const Args& A, int32_t w, const WordMeta& m)
+{
+    const uint4 a = m.a, b = m.b;
     WordSide v;
     v.kind = b.w;
     v.lg = b.z;
@@ -40,6 +52,12 @@ __device__ __forceinline__ WordSide load_word(const Args& A, int32_t w)
     else
         v.row = A.nkw + wk;
     return v;
+}
+
+template <int STORE, class Args>
+__device__ __forceinline__ WordSide load_word(const Args& A, int32_t w)
+{
+    return word_from_meta<STORE>(A, w, load_word_meta(A, w));
 }
 
 // n_kw[w][t] of a list-only word: bin i of its mixture table carries its i-th non-zero topic
@@ -111,6 +129,44 @@ __device__ __forceinline__ int32_t nkw_probe_finish(const WordSide& v, int32_t t
     const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
     const uint32_t mask = (1u << v.lg) - 1u;
     uint32_t s = (p.slot + 1) & mask;
+    for (uint32_t i = 1; i <= mask; ++i) {
+        const uint2 e = row[s];
+        if (e.x == (uint32_t)t) return (int32_t)e.y;
+        if (e.x == 0xFFFFFFFFu) return 0;
+        s = (s + 1) & mask;
+    }
+    return 0;
+}
+
+// The lookup as two dword loads from one computed address, whatever the kind of row (not for
+// list-only words): no branch between the loads of a round, so they are issued back to back.
+// Dense row: both loads read n_kw[t]; hash row: the slot's topic and count.
+struct NkwFetch {
+    uint32_t key, val, slot;
+};
+
+template <int STORE>
+__device__ __forceinline__ NkwFetch nkw_fetch_begin(const WordSide& v, int32_t t)
+{
+    const bool dense = STORE != 2 || (v.kind & 1u);
+    NkwFetch f;
+    f.slot = dense ? 0u : row_hash_slot(t, v.lg);
+    const uint32_t* __restrict__ base = static_cast<const uint32_t*>(v.row);
+    const size_t i = dense ? (size_t)t : 2 * (size_t)f.slot;
+    f.key = base[i];
+    f.val = base[dense ? i : i + 1];
+    return f;
+}
+
+template <int STORE>
+__device__ __forceinline__ int32_t nkw_fetch_finish(const WordSide& v, int32_t t, const NkwFetch& f)
+{
+    if (STORE != 2 || (v.kind & 1u)) return (int32_t)f.key;
+    if (f.key == (uint32_t)t) return (int32_t)f.val;
+    if (f.key == 0xFFFFFFFFu) return 0;
+    const uint2* __restrict__ row = static_cast<const uint2*>(v.row);
+    const uint32_t mask = (1u << v.lg) - 1u;
+    uint32_t s = (f.slot + 1) & mask;
     for (uint32_t i = 1; i <= mask; ++i) {
         const uint2 e = row[s];
         if (e.x == (uint32_t)t) return (int32_t)e.y;
