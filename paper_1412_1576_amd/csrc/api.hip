@@ -396,14 +396,13 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     // sweep tiling parameters (LDS: 12 bytes per token + 4 per document).  A packed n_kd
     // slot holds counts up to 4095, a token's slot index takes 12 bits and its document index
     // one byte, which bound the tile.
-    // default tile: 512 tokens / 256 threads; 1024 / 512 when the doc pass keeps n_k in LDS
-    // (the copy is made once per tile)
-    const bool big_tiles = K <= kNkLdsTopics;
-    c->chunk_tokens = o.sweep_chunk_tokens > 0 ? o.sweep_chunk_tokens : (big_tiles ? 1024 : 512);
+    // default tile: 1024 tokens / 512 threads, for every K (with n_k gathered from L2 instead
+    // of copied to LDS, 512-token tiles of 256 threads were a fifth slower at K = 10^5)
+    c->chunk_tokens = o.sweep_chunk_tokens > 0 ? o.sweep_chunk_tokens : 1024;
     c->chunk_tokens = std::max(64, std::min((c->chunk_tokens / 64) * 64, (int)kMaxTileTokens / 64 * 64));
     c->chunk_docs = std::max(16, std::min(255, c->chunk_tokens / 4));
     c->sweep_block = o.sweep_block_threads > 0 ? o.sweep_block_threads
-                                               : (big_tiles && o.sweep_chunk_tokens == 0 ? 512 : 256);
+                                               : (o.sweep_chunk_tokens == 0 ? 512 : 256);
     c->sweep_block = std::max(64, std::min(1024, (c->sweep_block / 64) * 64));
     // a thread carries at most 8 tokens of its tile
     c->sweep_block = std::max(c->sweep_block, ((c->chunk_tokens + 7) / 8 + 63) / 64 * 64);
@@ -437,7 +436,7 @@ int lda_init(lda_ctx** out, int64_t D, int32_t V, int32_t K, const int64_t* doc_
     // chains of one or two steps leave room for 768-thread workgroups on tiles of 1536 tokens
     // (measured: 7 % faster doc pass at K = 10 000); longer chains need the registers
     std::vector<int32_t> chunk_doc2;
-    if (big_tiles && o.sweep_chunk_tokens == 0 && o.sweep_block_threads == 0 && o.stream_block_tokens == 0) {
+    if (o.sweep_chunk_tokens == 0 && o.sweep_block_threads == 0 && o.stream_block_tokens == 0) {
         std::vector<int32_t> same_long;
         c->chunk_tokens2 = 1536;
         c->chunk_docs2 = 255;
