@@ -53,10 +53,10 @@ def doc_pass_bytes_per_token(mh_steps: int) -> float:
 # counter KiB x calibration factor x 1024, fetched + written); keyed by (workload, mh_steps,
 # dense_alias_min_count as passed to the library).  None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c3", 2, 10000): {"doc_pass_tiles_kernel": 49.79e9},
-    ("c2", 2, 1000): {"doc_pass_tiles_kernel": 6.73e9},
-    ("c4", 2, None): {"doc_pass_tiles_kernel": 89.22e9, "word_pass_gather_kernel": 127.13e9},
-    ("c5", 2, None): {"doc_pass_tiles_kernel": 104.62e9, "word_pass_gather_kernel": 199.59e9},
+    ("c3", 2, 10000): {"doc_pass_tiles_kernel": 48.70e9},
+    ("c2", 2, 1000): {"doc_pass_tiles_kernel": 6.59e9},
+    ("c4", 2, None): {"doc_pass_tiles_kernel": 75.05e9, "word_pass_gather_kernel": 50.33e9},
+    ("c5", 2, None): {"doc_pass_tiles_kernel": 92.44e9, "word_pass_gather_kernel": 147.41e9},
 }
 
 
