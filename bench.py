@@ -325,6 +325,10 @@ def main():
                 {}).get(dominant),
         },
     }
+    # the measured HBM-side bytes of the same kernel at this run's kernel time, next to the
+    # model figure: what really crossed the memory interface per second
+    if out["roofline"]["traffic"] and dom_ms:
+        out["roofline"]["traffic_GBs"] = out["roofline"]["traffic"] / (dom_ms * 1e-3) / 1e9
     g.close()
     if args.calibrate_copy:
         out["config"]["streaming_copy_GBs"] = copy_gbs
