@@ -73,14 +73,29 @@ __global__ __launch_bounds__(1024) void nkw_tiles_kernel(const RebuildTile* __re
     const int32_t k0 = (int32_t)blockIdx.y * span;
     const int32_t nk_r = ((k0 + span < K) ? k0 + span : K) - k0;
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
-    __syncthreads();
     auto count = [&](int32_t rec) {
         const uint32_t r = ((uint32_t)rec & zmask) - (uint32_t)k0;
         if (r < (uint32_t)nk_r) atomicAdd(&hist[r], 1);
     };
     auto at = [&](int32_t p) -> size_t { return xmap ? (size_t)xmap[p] : (size_t)p; };
     int32_t p = t.p0 + tid;
+    // The thread's first records are requested before the histogram is cleared: most tiles are
+    // short (a word of a thousand tokens), and the clearing and its barrier then hide the two
+    // dependent round trips instead of preceding them.  Threads past the end repeat the last.
+    int32_t first[2] = {0, 0};
+    if (t.p1 > t.p0) {  // (a word without tokens has an empty tile)
+        size_t q[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) q[u] = at(p + u * nt < t.p1 ? p + u * nt : t.p1 - 1);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) first[u] = __builtin_nontemporal_load(&zw[q[u] << sh]);
+    }
+    for (int32_t k = tid; k < nk_r; k += nt) hist[k] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+        if (p + u * nt < t.p1) count(first[u]);
+    p += 2 * nt;
     for (; p + 3 * nt < t.p1; p += 4 * nt) {  // four loads in flight per thread
         size_t q[4];
         int32_t rec[4];

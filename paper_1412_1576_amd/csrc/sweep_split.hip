@@ -601,23 +601,12 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
     const int4 it = A.mix_items[it_i];  // (w, p0, n, 0)
     const int32_t K = A.K, w = it.x;
     const int tid = threadIdx.x, nt = blockDim.x;
-    for (int32_t k = tid; k < K; k += nt) row[k] = 0;
-    __syncthreads();
-    {
-        const size_t off = A.sp_off[w];
-        const int32_t nnz = A.sp_nnz[w];
-        for (int32_t i = tid; i < nnz; i += nt) row[A.sp_topic[off + i]] = A.sp_count[off + i];
-    }
-    __syncthreads();
-    const WordSide wv = load_word<1>(A, w);
-    BetaTable bt{};
-    if constexpr (NW > 0) bt = load_beta_table(A);
     with_record_layout(A, [&](auto xm, auto p16) {
         constexpr int U = 2;
-        for (int32_t i0 = 0; i0 < it.z; i0 += U * nt) {
-            int32_t p[U], zt[U][1 + ND], out[U][C::R];
-            bool live[U];
-            TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
+        int32_t p[U];
+        bool live[U];
+        TokenFetch<ND, U, decltype(xm)::value, decltype(p16)::value> f;
+        auto place = [&](int32_t i0) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 int32_t i = i0 + u * nt + tid;
@@ -625,8 +614,30 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
                 if (!live[u]) i = it.z - 1;  // redo the item's last token, drop the result
                 p[u] = it.y + i;
             }
-            f.template positions<(NW > 0)>(A, p);
-            f.records(A);
+        };
+        // The first round's token loads and the thread's first list entry are requested before
+        // the row is built: they do not depend on it, and its two barriers hide their latency.
+        place(0);
+        f.template positions<(NW > 0)>(A, p);
+        f.records(A);
+        const size_t off = A.sp_off[w];
+        const int32_t nnz = A.sp_nnz[w];
+        const int32_t i_first = tid < nnz ? tid : (nnz > 0 ? nnz - 1 : 0);
+        int32_t tp0 = 0, ct0 = 0;
+        if (nnz > 0) {
+            tp0 = A.sp_topic[off + i_first];
+            ct0 = A.sp_count[off + i_first];
+        }
+        const WordSide wv = load_word<1>(A, w);
+        BetaTable bt{};
+        if constexpr (NW > 0) bt = load_beta_table(A);
+        for (int32_t k = tid; k < K; k += nt) row[k] = 0;
+        __syncthreads();
+        if (nnz > 0) row[tp0] = ct0;  // threads past the list's end repeat its last entry
+        for (int32_t i = tid + nt; i < nnz; i += nt) row[A.sp_topic[off + i]] = A.sp_count[off + i];
+        __syncthreads();
+        for (int32_t i0 = 0;;) {
+            int32_t zt[U][1 + ND], out[U][C::R];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 f.decode(u, zt[u]);
@@ -660,6 +671,11 @@ __global__ __launch_bounds__(512) void word_pass_mix_rows_kernel(SplitArgs A)
                 for (int k = 0; k < ND; ++k) out[u][C::rec_doc(k)] = row[zt[u][1 + k]];
                 if (live[u]) store_ints<C::R>(A.rec + (f.q[u] << C::rec_shift), out[u]);
             }
+            i0 += U * nt;
+            if (i0 >= it.z) break;
+            place(i0);
+            f.template positions<(NW > 0)>(A, p);
+            f.records(A);
         }
     });
 }
