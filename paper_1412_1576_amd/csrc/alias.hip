@@ -6,6 +6,8 @@
 // beta/(n_k + betabar); the sweep picks the term by the two integer masses QS_w and QB.
 // Every table is built by one workgroup with the generic builder of alias_build.hpp;
 // tables too large for LDS use a global workspace.
+#include <algorithm>
+
 #include "alias_build.hpp"
 
 namespace lda {
@@ -183,7 +185,8 @@ __device__ __forceinline__ void mix_table(const MixArgs& a, int32_t w, unsigned 
         a.metaA[2 * (size_t)w] = make_uint4((uint32_t)n, C, (uint32_t)QS, (uint32_t)(QS >> 32));
 }
 
-__global__ __launch_bounds__(256) void alias_mix_lds_kernel(MixArgs a)
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void alias_mix_lds_kernel(MixArgs a)
 {
     extern __shared__ unsigned char smem_raw[];
     mix_table<false>(a, a.words[blockIdx.x], smem_raw);
@@ -354,11 +357,24 @@ int launch_alias_mix_class(lda_ctx* c, hipStream_t stream, const int32_t* words,
     if (cap_entries > 0) {
         size_t lds;
         lds_plan((size_t)cap_entries, lds, a.use_cache);
-        int rc = set_lds(c, alias_mix_lds_kernel, lds);
-        if (rc != LDA_OK) return rc;
-        int threads = ((cap_entries + kWave - 1) / kWave) * kWave;
-        if (threads > 256) threads = 256;
-        hipLaunchKernelGGL(alias_mix_lds_kernel, dim3(n_words), dim3(threads), lds, stream, a);
+        // Tables of a few thousand entries are few per CU (their lists fill the LDS), so each
+        // gets more waves: the time of one table, not the number in flight, bounds such a class.
+        // (c3: 2.95 -> 2.57 ms for all tables, c4: 10.9 -> 10.1)
+        if (cap_entries >= 2048) {
+            int rc = set_lds(c, alias_mix_lds_kernel<1024>, lds);
+            if (rc != LDA_OK) return rc;
+            int threads = cap_entries / 4;
+            threads = threads < 256 ? 256 : (threads > 1024 ? 1024 : threads / kWave * kWave);
+            hipLaunchKernelGGL(alias_mix_lds_kernel<1024>, dim3(n_words), dim3(threads), lds, stream, a);
+        } else {
+            int rc = set_lds(c, alias_mix_lds_kernel<256>, lds);
+            if (rc != LDA_OK) return rc;
+            // small tables: half a wave's worth of entries per lane-round keeps more tables in
+            // flight (two waves per table up to 1024 entries; c2 0.62 -> 0.51 ms, c4 10.0 -> 9.6)
+            int threads = ((cap_entries + kWave - 1) / kWave) * kWave;
+            threads = std::max(64, std::min(threads, 256) / 2 / kWave * kWave);
+            hipLaunchKernelGGL(alias_mix_lds_kernel<256>, dim3(n_words), dim3(threads), lds, stream, a);
+        }
     } else {
         a.use_cache = 1; a.ws = c->d_big_ws; a.ws_stride = c->big_ws_stride;
         a.next = c->d_flag + 1;
