@@ -162,8 +162,8 @@ def run_leg(workload, mh_steps, steps, warmup, dense_alias_min_count, corpora, s
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--mh-steps", type=int, default=2)
     ap.add_argument("--docs", type=int, default=0, help="use only the first DOCS documents' worth "
